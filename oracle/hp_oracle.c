@@ -1,0 +1,290 @@
+/*
+ * CPU oracle for the boundary layout transform.  TEST INFRASTRUCTURE ONLY:
+ * nothing in the product path may call, link or import this file; it exists so
+ * that tests, the smoke check and the benchmark's cpu_baseline leg have an
+ * independent statement of what the transform computes.  It shares no code,
+ * header, table or helper with the HIP library.
+ *
+ * What is computed (paper, Method section): a boundary edge u -> v carries one
+ * tensor with two distributed representations.  Forward materialises the
+ * source-layout activation in the destination layout; backward applies the
+ * reverse transform so that gradients return to the source layout.  Here the
+ * source is a vision encoder whose data-parallel ranks each hold the projected
+ * tokens of a contiguous run of images (the "batch intervals" of the logical
+ * batch-shard transform, Method section), and the destination is the language
+ * model: the tokens are inserted into the fused input sequence at the image
+ * positions (Fig. 1 caption; "Pipeline schedule details": the first LLM stage
+ * inserts the boundary view into the microbatch's text embeddings), the fused
+ * sequence is split over the LLM's context-parallel ranks (Intro: CP shards the
+ * fused language sequence) and every tensor-parallel rank of the receiving group
+ * holds the activation (Non-colocated communicator: local TP/CP broadcast to
+ * the non-leader ranks).
+ *
+ * Everything is written pull-style, one destination row at a time, by walking
+ * the layout definitions; there is no blocking, caching or inverse table.
+ *
+ * Conventions the paper leaves open and this build fixes (all are restated in
+ * the design notes):
+ *   - rank order inside a grid: tp fastest, then cp, then dp;
+ *   - the unit of the source batch intervals is one image; by default source dp
+ *     rank d holds images [floor(d*K/DP), floor((d+1)*K/DP)) of the K images in
+ *     global order, or the caller gives the assignment explicitly;
+ *   - source TP ranks hold identical replicas; forward reads replica 0 (the
+ *     boundary leader), backward writes all of them;
+ *   - sequence split: contiguous (rank r holds [r*S/C,(r+1)*S/C)) or
+ *     load-balanced "zigzag" (2C equal chunks, rank r holds chunk r followed by
+ *     chunk 2C-1-r);
+ *   - local memory order of a destination buffer: [B_local, S_local, H] or
+ *     [S_local, B_local, H];
+ *   - sequence-sharded destination TP (tp_mode 1): the S_local positions of a
+ *     CP rank are cut into TP equal contiguous pieces, TP rank t holds piece t,
+ *     and no row is replicated;
+ *   - backward over the destination TP replicas is a SUM (the adjoint of
+ *     replication), a left fold in ascending tp order in IEEE binary32 with
+ *     round-to-nearest-even and subnormals kept, then one rounding to bf16
+ *     (round-to-nearest-even, NaN stays NaN).  The paper itself forwards the
+ *     leader's gradient without a reduction (Non-colocated communicator,
+ *     backward paragraph); the sum is this build's stated target.
+ *
+ * parity unpinned: the image->rank rule, the rank order and the row order are
+ * conventions of this build; no passage of the paper fixes them.  They are
+ * pinned only by the brute-force slicing tests and by the reduction to equal
+ * per-sample batch intervals when images per sample are constant.
+ */
+#include <stdint.h>
+#include <stddef.h>
+#include <string.h>
+
+typedef struct {
+    int32_t tp, cp, dp;
+    int32_t tp_mode;   /* 0 replicate, 1 sequence-sharded (destination only) */
+    int32_t cp_split;  /* 0 contiguous, 1 zigzag (destination only)          */
+    int32_t row_order; /* 0 [B,S,H], 1 [S,B,H] (destination only)            */
+} orc_grid_t;
+
+typedef struct {
+    int32_t batch, seq, hidden;
+    int32_t n_images;
+    const int32_t *img_sample, *img_start, *img_len;
+    const int32_t *img_src_dp; /* NULL: balanced contiguous intervals */
+} orc_map_t;
+
+/* ---- bf16 <-> binary32 -------------------------------------------------- */
+
+static float bf16_to_f32(uint16_t h)
+{
+    uint32_t u = (uint32_t)h << 16;
+    float f;
+    memcpy(&f, &u, 4);
+    return f;
+}
+
+/* Round-to-nearest-even on the upper 16 bits; NaN keeps its sign and upper
+ * payload and is forced quiet so that it cannot round to infinity. */
+static uint16_t f32_to_bf16(float f)
+{
+    uint32_t u;
+    memcpy(&u, &f, 4);
+    if ((u & 0x7fffffffu) > 0x7f800000u)
+        return (uint16_t)((u >> 16) | 0x0040u);
+    uint32_t lower = u & 0xffffu, upper = u >> 16;
+    if (lower > 0x8000u || (lower == 0x8000u && (upper & 1u)))
+        upper += 1u;
+    return (uint16_t)upper;
+}
+
+uint16_t orc_f32_to_bf16(float f) { return f32_to_bf16(f); }
+float orc_bf16_to_f32(uint16_t h) { return bf16_to_f32(h); }
+
+/* ---- source side -------------------------------------------------------- */
+
+/* Source dp rank that holds image k. */
+int32_t orc_image_src_dp(const orc_grid_t *src, const orc_map_t *m, int32_t k)
+{
+    if (m->img_src_dp)
+        return m->img_src_dp[k];
+    int64_t K = m->n_images;
+    for (int32_t d = 0; d < src->dp; ++d) {
+        int64_t lo = ((int64_t)d * K) / src->dp;
+        int64_t hi = ((int64_t)(d + 1) * K) / src->dp;
+        if (k >= lo && k < hi)
+            return d;
+    }
+    return -1;
+}
+
+/* Rows held by every TP replica of source dp rank d: the images assigned to d,
+ * concatenated in global image order. */
+int64_t orc_src_rows(const orc_grid_t *src, const orc_map_t *m, int32_t d)
+{
+    int64_t rows = 0;
+    for (int32_t k = 0; k < m->n_images; ++k)
+        if (orc_image_src_dp(src, m, k) == d)
+            rows += m->img_len[k];
+    return rows;
+}
+
+/* Where token j of image k lives on the source side. */
+static void src_locate(const orc_grid_t *src, const orc_map_t *m, int32_t k, int32_t j,
+                       int32_t *d_out, int64_t *row_out)
+{
+    int32_t d = orc_image_src_dp(src, m, k);
+    int64_t off = 0;
+    for (int32_t e = 0; e < k; ++e)
+        if (orc_image_src_dp(src, m, e) == d)
+            off += m->img_len[e];
+    *d_out = d;
+    *row_out = off + j;
+}
+
+/* ---- destination side --------------------------------------------------- */
+
+int64_t orc_dst_rows(const orc_grid_t *dst, const orc_map_t *m)
+{
+    int64_t bl = m->batch / dst->dp;
+    int64_t sl = m->seq / dst->cp;
+    if (dst->tp_mode == 1)
+        sl /= dst->tp;
+    return bl * sl;
+}
+
+/* Global (sample, position) of local row `row` of destination buffer `buf`
+ * (buf = tp + TP*(cp + CP*dp)). */
+static void dst_global(const orc_grid_t *dst, const orc_map_t *m, int32_t buf, int64_t row,
+                       int32_t *b_out, int64_t *s_out)
+{
+    int32_t tp = buf % dst->tp;
+    int32_t cp = (buf / dst->tp) % dst->cp;
+    int32_t dp = buf / (dst->tp * dst->cp);
+    int64_t bl_n = m->batch / dst->dp;       /* samples per dp rank            */
+    int64_t scp = m->seq / dst->cp;          /* positions per cp rank          */
+    int64_t sl_n = scp;                      /* positions in this buffer       */
+    if (dst->tp_mode == 1)
+        sl_n = scp / dst->tp;
+    int64_t b_l, s_l;
+    if (dst->row_order == 0) { b_l = row / sl_n; s_l = row % sl_n; }
+    else                     { s_l = row / bl_n; b_l = row % bl_n; }
+    if (dst->tp_mode == 1)
+        s_l += (int64_t)tp * sl_n;           /* piece tp of the cp-local run   */
+    int64_t s;
+    if (dst->cp_split == 0) {
+        s = (int64_t)cp * scp + s_l;
+    } else {
+        int64_t c = m->seq / (2 * (int64_t)dst->cp);
+        if (s_l < c) s = (int64_t)cp * c + s_l;
+        else         s = (2 * (int64_t)dst->cp - 1 - cp) * c + (s_l - c);
+    }
+    *b_out = (int32_t)(dp * bl_n + b_l);
+    *s_out = s;
+}
+
+/* Image covering (b, s), if any. */
+static int find_image(const orc_map_t *m, int32_t b, int64_t s, int32_t *k_out, int32_t *j_out)
+{
+    for (int32_t k = 0; k < m->n_images; ++k) {
+        if (m->img_sample[k] != b) continue;
+        if (s >= m->img_start[k] && s < (int64_t)m->img_start[k] + m->img_len[k]) {
+            *k_out = k;
+            *j_out = (int32_t)(s - m->img_start[k]);
+            return 1;
+        }
+    }
+    return 0;
+}
+
+static int check_shapes(const orc_grid_t *src, const orc_grid_t *dst, const orc_map_t *m)
+{
+    if (src->tp < 1 || src->dp < 1 || dst->tp < 1 || dst->cp < 1 || dst->dp < 1) return -1;
+    if (m->batch % dst->dp) return -1;
+    if (m->seq % dst->cp) return -1;
+    if (dst->cp_split == 1 && m->seq % (2 * dst->cp)) return -1;
+    if (dst->tp_mode == 1 && (m->seq / dst->cp) % dst->tp) return -1;
+    return 0;
+}
+
+/* For every local row of destination buffer `buf`: the source buffer index
+ * (replica 0: dp*TPs) and source row that forward copies there, or -1/-1 for a
+ * text row.  Arrays hold orc_dst_rows() entries. */
+int orc_forward_map(const orc_grid_t *src, const orc_grid_t *dst, const orc_map_t *m,
+                    int32_t buf, int32_t *src_buf, int64_t *src_row)
+{
+    if (check_shapes(src, dst, m)) return -1;
+    int64_t rows = orc_dst_rows(dst, m);
+    for (int64_t r = 0; r < rows; ++r) {
+        int32_t b, k, j, d; int64_t s, srow;
+        dst_global(dst, m, buf, r, &b, &s);
+        if (find_image(m, b, s, &k, &j)) {
+            src_locate(src, m, k, j, &d, &srow);
+            src_buf[r] = d * src->tp;
+            src_row[r] = srow;
+        } else {
+            src_buf[r] = -1;
+            src_row[r] = -1;
+        }
+    }
+    return 0;
+}
+
+/* Forward.  src_bufs[tp + TPs*dp] -> dst_bufs[tp + TPd*(cp + CPd*dp)]; rows of
+ * `elem_size * hidden` bytes are moved bit for bit.  Only image-token rows of
+ * the destination are written. */
+int orc_forward(const orc_grid_t *src, const orc_grid_t *dst, const orc_map_t *m,
+                int32_t elem_size, const void *const *src_bufs, void *const *dst_bufs)
+{
+    if (check_shapes(src, dst, m)) return -1;
+    const size_t row_bytes = (size_t)elem_size * (size_t)m->hidden;
+    const int32_t n_dst = dst->tp * dst->cp * dst->dp;
+    const int64_t rows = orc_dst_rows(dst, m);
+    const int64_t total = (int64_t)n_dst * rows;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < total; ++i) {
+        int32_t buf = (int32_t)(i / rows);
+        int64_t r = i % rows;
+        int32_t b, k, j, d; int64_t s, srow;
+        dst_global(dst, m, buf, r, &b, &s);
+        if (!find_image(m, b, s, &k, &j)) continue;       /* text row: untouched */
+        src_locate(src, m, k, j, &d, &srow);
+        const char *from = (const char *)src_bufs[d * src->tp + 0] + (size_t)srow * row_bytes;
+        char *to = (char *)dst_bufs[buf] + (size_t)r * row_bytes;
+        memcpy(to, from, row_bytes);
+    }
+    return 0;
+}
+
+/* Backward (bf16 in, binary32 accumulate, bf16 out).  For every image-token row
+ * of every (dp, cp[, tp piece]) destination slice: fold the TP replicas of the
+ * gradient in ascending tp order, round once, and store the result into every
+ * TP replica of the source rank that supplied the row in forward.  In
+ * sequence-sharded mode there is one copy per row and the fold has one term.
+ * Gradients on text rows are ignored. */
+int orc_backward_bf16(const orc_grid_t *src, const orc_grid_t *dst, const orc_map_t *m,
+                      const uint16_t *const *dst_grads, uint16_t *const *src_grads)
+{
+    if (check_shapes(src, dst, m)) return -1;
+    const int64_t H = m->hidden;
+    const int32_t n_dst = dst->tp * dst->cp * dst->dp;
+    const int64_t rows = orc_dst_rows(dst, m);
+    const int32_t n_rep = dst->tp_mode == 1 ? 1 : dst->tp;   /* copies of each row */
+    const int32_t n_slices = n_dst / n_rep;                  /* buffers that differ */
+    const int64_t total = (int64_t)n_slices * rows;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < total; ++i) {
+        int32_t buf0 = (int32_t)(i / rows) * n_rep;          /* replica tp = 0      */
+        int64_t r = i % rows;
+        int32_t b, k, j, d; int64_t s, srow;
+        dst_global(dst, m, buf0, r, &b, &s);
+        if (!find_image(m, b, s, &k, &j)) continue;
+        src_locate(src, m, k, j, &d, &srow);
+        for (int64_t h = 0; h < H; ++h) {
+            volatile float acc = bf16_to_f32(dst_grads[buf0][r * H + h]);
+            for (int32_t t = 1; t < n_rep; ++t) {
+                float g = bf16_to_f32(dst_grads[buf0 + t][r * H + h]);
+                acc = acc + g;
+            }
+            uint16_t out = f32_to_bf16(acc);
+            for (int32_t ts = 0; ts < src->tp; ++ts)
+                src_grads[d * src->tp + ts][srow * H + h] = out;
+        }
+    }
+    return 0;
+}

@@ -1,0 +1,520 @@
+"""Pins for the CPU oracle: everything here runs without a GPU and checks the
+oracle against things other than itself - hand-worked fixtures, a brute-force
+"build the global tensors and slice them" formulation, library routines
+(memcpy-like identity, torch.index_copy_, torch's bf16 cast, numpy float32
+addition), closed forms and invariants."""
+import json
+import os
+import struct
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import oracle
+from paper_2605_27678_amd import workloads as wl
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+# ----------------------------------------------------------------------------
+# brute force: materialise the global boundary tensor X and the global fused
+# tensor, then cut the destination buffers out of it with array slicing.
+# ----------------------------------------------------------------------------
+
+def default_src_dp(k_images, dp):
+    """Closed form of the balanced contiguous interval rule: image k is on
+    rank ceil((k+1)*DP/K) - 1."""
+    k = np.arange(k_images, dtype=np.int64)
+    return (((k + 1) * dp + k_images - 1) // k_images - 1).astype(np.int32) if k_images else k.astype(np.int32)
+
+
+def brute_sources(src, tm, X):
+    """Split X (rows in global image order) into the source buffers."""
+    dps = tm.img_src_dp if tm.img_src_dp is not None else default_src_dp(tm.n_images, src.dp)
+    bounds = np.concatenate([[0], np.cumsum(tm.img_len.astype(np.int64))])
+    bufs = []
+    for d in range(src.dp):
+        parts = [X[bounds[k]:bounds[k + 1]] for k in range(tm.n_images) if dps[k] == d]
+        rows = np.concatenate(parts, axis=0) if parts else X[:0]
+        for _ in range(src.tp):
+            bufs.append(rows.copy())
+    return bufs
+
+
+def brute_slice(dst, tm, G):
+    """Cut a global [B, S, ...] array into the destination buffers."""
+    B, S = tm.batch, tm.seq
+    bl = B // dst.dp
+    out = []
+    for dp in range(dst.dp):
+        slab = G[dp * bl:(dp + 1) * bl]
+        for cp in range(dst.cp):
+            if dst.cp_split == wl.CP_CONTIGUOUS:
+                sl = S // dst.cp
+                loc = slab[:, cp * sl:(cp + 1) * sl]
+            else:
+                c = S // (2 * dst.cp)
+                chunks = slab.reshape((bl, 2 * dst.cp, c) + G.shape[2:])
+                loc = np.concatenate([chunks[:, cp], chunks[:, 2 * dst.cp - 1 - cp]], axis=1)
+            for tp in range(dst.tp):
+                piece = loc
+                if dst.tp_mode == wl.TP_SEQ_SHARD:
+                    w = loc.shape[1] // dst.tp
+                    piece = loc[:, tp * w:(tp + 1) * w]
+                if dst.row_order == wl.ROW_SBH:
+                    piece = np.swapaxes(piece, 0, 1)
+                out.append(np.ascontiguousarray(piece).reshape((-1,) + G.shape[2:]))
+    # the loops above ran dp, cp, tp with tp innermost: index = tp + TP*(cp + CP*dp)
+    return out
+
+
+def brute_forward(src, dst, tm, X, text_value):
+    H = X.shape[1]
+    fused = np.full((tm.batch, tm.seq, H), text_value, dtype=X.dtype)
+    is_img = np.zeros((tm.batch, tm.seq), dtype=bool)
+    n = 0
+    for k in range(tm.n_images):
+        b, s, ln = int(tm.img_sample[k]), int(tm.img_start[k]), int(tm.img_len[k])
+        fused[b, s:s + ln] = X[n:n + ln]
+        is_img[b, s:s + ln] = True
+        n += ln
+    return brute_slice(dst, tm, fused), brute_slice(dst, tm, is_img)
+
+
+def row_id_payload(n_rows, hidden):
+    """X[n, h] = 64*n + h in uint16: every element names its own row/column."""
+    assert hidden <= 64 and n_rows * 64 < 65536
+    return (64 * np.arange(n_rows, dtype=np.uint32)[:, None] + np.arange(hidden)[None, :]).astype(np.uint16)
+
+
+def run_oracle_forward(src, dst, tm, X, text_value=0xFFFF):
+    prob = oracle.Problem(src, dst, tm)
+    srcs = brute_sources(src, tm, X)
+    assert [a.shape[0] for a in srcs] == prob.src_rows()
+    dsts = [np.full((prob.dst_rows(), tm.hidden), text_value, dtype=X.dtype) for _ in range(prob.n_dst)]
+    prob.forward(srcs, dsts)
+    return prob, srcs, dsts
+
+
+# ----------------------------------------------------------------------------
+# hand-worked fixture
+# ----------------------------------------------------------------------------
+
+def _grid_from(d, **kw):
+    return wl.Grid(tp=d.get("tp", 1), cp=d.get("cp", 1), dp=d.get("dp", 1),
+                   cp_split=wl.CP_ZIGZAG if d.get("cp_split") == "zigzag" else wl.CP_CONTIGUOUS,
+                   row_order=wl.ROW_SBH if d.get("row_order") == "sbh" else wl.ROW_BSH, **kw)
+
+
+def _bf16_bits(vals):
+    return wl.bf16_bits(torch.tensor(vals, dtype=torch.float32).to(torch.bfloat16)).copy()
+
+
+def test_worked_example_forward_and_backward():
+    g = json.load(open(os.path.join(GOLDEN, "worked_example_zigzag.json")))
+    src, dst = _grid_from(g["src"]), _grid_from(g["dst"])
+    tm = wl.TokenMap(g["batch"], g["seq"], g["hidden"], g["img_sample"], g["img_start"], g["img_len"])
+    prob = oracle.Problem(src, dst, tm)
+    assert prob.src_rows() == [len(b) for b in g["src_bufs"]]
+    srcs = [_bf16_bits(b).reshape(-1, 1) for b in g["src_bufs"]]
+    dsts = [_bf16_bits([g["dst_text"]] * prob.dst_rows()).reshape(-1, 1) for _ in range(prob.n_dst)]
+    prob.forward(srcs, dsts)
+    for j in range(prob.n_dst):
+        assert dsts[j].ravel().tolist() == _bf16_bits(g["dst_expected"][str(j)]).tolist(), j
+    grads = [_bf16_bits(g["dst_grads"][str(j)]).reshape(-1, 1) for j in range(prob.n_dst)]
+    sg = [np.full((r, 1), 0x7FC1, np.uint16) for r in prob.src_rows()]
+    prob.backward_bf16(grads, sg)
+    for i, exp in enumerate(g["src_grads_expected"]):
+        assert sg[i].ravel().tolist() == _bf16_bits(exp).tolist(), i
+
+
+def test_zigzag_positions_closed_form():
+    """Rank r of C holds chunk r then chunk 2C-1-r; together the ranks tile
+    [0, S) exactly once."""
+    for C in (1, 2, 4, 8):
+        S = 2 * C * 3
+        tm = wl.TokenMap(1, S, 1, [0], [0], [S])          # one image covering everything
+        src, dst = wl.Grid(), wl.Grid(cp=C, cp_split=wl.CP_ZIGZAG)
+        prob = oracle.Problem(src, dst, tm)
+        seen = []
+        for r in range(C):
+            _, rows = prob.forward_map(r)                 # source row == global position
+            c = S // (2 * C)
+            expect = list(range(r * c, (r + 1) * c)) + list(range((2 * C - 1 - r) * c, (2 * C - r) * c))
+            assert rows.tolist() == expect
+            seen += rows.tolist()
+        assert sorted(seen) == list(range(S))
+
+
+# ----------------------------------------------------------------------------
+# brute force on many tiny layouts
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", range(60))
+def test_forward_matches_global_slicing(seed):
+    rng = np.random.default_rng(1000 + seed)
+    src, dst, tm = wl.random_layout_case(rng)
+    X = row_id_payload(tm.n_rows, tm.hidden)
+    prob, srcs, dsts = run_oracle_forward(src, dst, tm, X)
+    want, is_img = brute_forward(src, dst, tm, X, 0xFFFF)
+    assert len(want) == prob.n_dst
+    for j in range(prob.n_dst):
+        assert np.array_equal(dsts[j], want[j]), (seed, j)
+    # bytes conserved: image rows over all destination buffers = TP_dst * N
+    assert sum(int(m.sum()) for m in is_img) == dst.tp * tm.n_rows
+    assert sum(a.shape[0] for a in srcs) == src.tp * tm.n_rows
+
+
+@pytest.mark.parametrize("seed", range(20))
+def test_forward_matches_global_slicing_seq_sharded(seed):
+    rng = np.random.default_rng(5000 + seed)
+    src, dst, tm = wl.random_layout_case(rng)
+    from dataclasses import replace
+    if (tm.seq // dst.cp) % dst.tp:
+        dst = replace(dst, tp=2 if (tm.seq // dst.cp) % 2 == 0 else 1)
+    dst = replace(dst, tp_mode=wl.TP_SEQ_SHARD)
+    X = row_id_payload(tm.n_rows, tm.hidden)
+    prob, srcs, dsts = run_oracle_forward(src, dst, tm, X)
+    want, is_img = brute_forward(src, dst, tm, X, 0xFFFF)
+    for j in range(prob.n_dst):
+        assert np.array_equal(dsts[j], want[j]), (seed, j)
+    assert sum(int(m.sum()) for m in is_img) == tm.n_rows       # nothing replicated
+
+
+def test_paper_layout_pairs():
+    """Layout pairs that appear in the paper (user configuration example: LLM
+    TP4 DP2 with vision TP1 DP8 colocated, LLM TP2 with vision DP4 disjoint;
+    bridge profile: encoder DP32 -> LLM DP16)."""
+    pairs = [(wl.Grid(tp=1, dp=8), wl.Grid(tp=4, dp=2), 8, 4),
+             (wl.Grid(tp=1, dp=4, rank_offset=4), wl.Grid(tp=2, dp=1), 4, 2),
+             (wl.Grid(tp=1, dp=32), wl.Grid(tp=1, dp=16), 32, 1)]
+    for src, dst, batch, imgs in pairs:
+        rng = np.random.default_rng(7)
+        tm = wl.token_map_from_lens(rng, batch, 24, 8, [[3] * imgs] * batch)
+        X = row_id_payload(tm.n_rows, tm.hidden)
+        prob, srcs, dsts = run_oracle_forward(src, dst, tm, X)
+        want, _ = brute_forward(src, dst, tm, X, 0xFFFF)
+        for j in range(prob.n_dst):
+            assert np.array_equal(dsts[j], want[j])
+
+
+def test_fan_in_two_quarter_shards_make_one_half_shard():
+    """Figures 2 and 3: with B samples, source DP4 and destination DP2, source
+    shards 0,1 (B/4 each) are concatenated in batch order into destination
+    shard 0, shards 2,3 into shard 1; backward splits along the same
+    intervals."""
+    B, L = 4, 6
+    tm = wl.TokenMap(B, L, 4, list(range(B)), [0] * B, [L] * B)   # all-image samples
+    src, dst = wl.Grid(dp=4), wl.Grid(dp=2)
+    X = row_id_payload(B * L, 4)
+    prob, srcs, dsts = run_oracle_forward(src, dst, tm, X)
+    assert prob.src_rows() == [L] * 4                      # equal B/4 batch intervals
+    assert np.array_equal(dsts[0], np.concatenate([srcs[0], srcs[1]]))
+    assert np.array_equal(dsts[1], np.concatenate([srcs[2], srcs[3]]))
+    g = [row_id_payload(2 * L, 4) + np.uint16(j) for j in range(2)]   # any bf16 bit patterns, no NaN
+    g = [np.where((x & 0x7F80) == 0x7F80, np.uint16(0), x) for x in g]
+    sg = [np.zeros((L, 4), np.uint16) for _ in range(4)]
+    prob.backward_bf16(g, sg)
+    assert np.array_equal(sg[0], g[0][:L]) and np.array_equal(sg[1], g[0][L:])
+    assert np.array_equal(sg[2], g[1][:L]) and np.array_equal(sg[3], g[1][L:])
+
+
+def test_fan_out_dual_case():
+    """Dual case of the figures: one B/2 source shard is split into two B/4
+    destination shards; backward concatenates the sibling gradients."""
+    B, L = 4, 5
+    tm = wl.TokenMap(B, L, 4, list(range(B)), [0] * B, [L] * B)
+    src, dst = wl.Grid(dp=2), wl.Grid(dp=4)
+    X = row_id_payload(B * L, 4)
+    prob, srcs, dsts = run_oracle_forward(src, dst, tm, X)
+    assert prob.src_rows() == [2 * L] * 2
+    for j in range(4):
+        assert np.array_equal(dsts[j], srcs[j // 2][(j % 2) * L:(j % 2 + 1) * L])
+    g = [np.full((L, 4), 0x3F80 + j, np.uint16) for j in range(4)]
+    sg = [np.zeros((2 * L, 4), np.uint16) for _ in range(2)]
+    prob.backward_bf16(g, sg)
+    assert np.array_equal(sg[0], np.concatenate([g[0], g[1]]))
+    assert np.array_equal(sg[1], np.concatenate([g[2], g[3]]))
+
+
+def test_default_image_rule_reduces_to_equal_batch_intervals():
+    """With a constant number of images per sample and DP dividing B, the
+    image-unit rule is the paper's equal batch intervals: sample b is on source
+    rank b // (B/DP)."""
+    B, per, dp = 8, 3, 4
+    rng = np.random.default_rng(3)
+    tm = wl.token_map_from_lens(rng, B, 40, 8, [[4] * per] * B)
+    prob = oracle.Problem(wl.Grid(dp=dp), wl.Grid(), tm)
+    L = oracle.lib()
+    import ctypes as C
+    for k in range(tm.n_images):
+        d = L.orc_image_src_dp(C.byref(prob.src), C.byref(prob.map), C.c_int32(k))
+        assert d == int(tm.img_sample[k]) // (B // dp)
+    # ragged counts: closed form of the same interval rule, ranks may be empty
+    for K, dpn in [(5, 2), (3, 8), (31, 8), (1, 4), (7, 7)]:
+        tm2 = wl.TokenMap(1, 4 * K, 8, [0] * K, [4 * i for i in range(K)], [4] * K)
+        p2 = oracle.Problem(wl.Grid(dp=dpn), wl.Grid(), tm2)
+        got = [L.orc_image_src_dp(C.byref(p2.src), C.byref(p2.map), C.c_int32(k)) for k in range(K)]
+        assert got == default_src_dp(K, dpn).tolist()
+        assert got == sorted(got) and all(0 <= d < dpn for d in got)
+
+
+def test_identity_layout_is_memcpy():
+    tm = wl.TokenMap(1, 37, 24, [0], [0], [37])
+    X = np.random.default_rng(0).integers(0, 65536, size=(37, 24), dtype=np.uint16)
+    prob, srcs, dsts = run_oracle_forward(wl.Grid(), wl.Grid(), tm, X)
+    assert dsts[0].tobytes() == X.tobytes()
+
+
+def test_single_sample_equals_index_copy():
+    """No CP, one sample: forward is torch.index_copy_ of X into the sequence at
+    the image positions."""
+    rng = np.random.default_rng(11)
+    tm = wl.token_map_from_lens(rng, 1, 200, 16, [[7, 30, 1, 19]])
+    X = rng.integers(0, 30000, size=(tm.n_rows, 16)).astype(np.int16)
+    prob, srcs, dsts = run_oracle_forward(wl.Grid(dp=3), wl.Grid(tp=2), tm, X.view(np.uint16), text_value=5)
+    pos = np.concatenate([np.arange(s, s + l) for s, l in zip(tm.img_start, tm.img_len)])
+    seq = torch.full((200, 16), 5, dtype=torch.int16)
+    seq.index_copy_(0, torch.from_numpy(pos), torch.from_numpy(X))
+    for j in range(2):
+        assert np.array_equal(dsts[j].view(np.int16), seq.numpy())
+
+
+def test_other_element_sizes_move_bit_for_bit():
+    rng = np.random.default_rng(5)
+    src, dst, tm = wl.random_layout_case(rng)
+    for dt in (np.uint8, np.uint32, np.float64):
+        X = rng.integers(0, 255, size=(tm.n_rows, tm.hidden)).astype(dt)
+        prob = oracle.Problem(src, dst, tm)
+        srcs = brute_sources(src, tm, X)
+        dsts = [np.full((prob.dst_rows(), tm.hidden), 77, dtype=dt) for _ in range(prob.n_dst)]
+        prob.forward(srcs, dsts)
+        want, _ = brute_forward(src, dst, tm, X, 77)
+        for j in range(prob.n_dst):
+            assert np.array_equal(dsts[j], want[j])
+
+
+# ----------------------------------------------------------------------------
+# invariants
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", range(25))
+def test_forward_map_is_injective_and_invertible(seed):
+    """Restricted to one TP replica, forward is a bijection between the image
+    rows of the source side and the image rows of the destination side;
+    applying the inverse after it gives the identity."""
+    rng = np.random.default_rng(2000 + seed)
+    src, dst, tm = wl.random_layout_case(rng)
+    prob = oracle.Problem(src, dst, tm)
+    pairs = {}
+    for j in range(0, prob.n_dst, dst.tp):                # replica tp = 0 of every slice
+        sb, sr = prob.forward_map(j)
+        for t in range(1, dst.tp):                        # replicas agree
+            sb2, sr2 = prob.forward_map(j + t)
+            assert np.array_equal(sb, sb2) and np.array_equal(sr, sr2)
+        for r in np.nonzero(sb >= 0)[0]:
+            key = (int(sb[r]), int(sr[r]))
+            assert key not in pairs                       # injective
+            pairs[key] = (j, int(r))
+    rows = prob.src_rows()
+    want = {(i, r) for i in range(0, prob.n_src, src.tp) for r in range(rows[i])}
+    assert set(pairs) == want                             # onto the source rows
+    # inverse after forward = identity, shown on data
+    X = row_id_payload(tm.n_rows, tm.hidden)
+    srcs = brute_sources(src, tm, X)
+    dsts = [np.zeros((prob.dst_rows(), tm.hidden), np.uint16) for _ in range(prob.n_dst)]
+    prob.forward(srcs, dsts)
+    back = [np.zeros_like(a) for a in srcs]
+    for (i, r), (j, q) in pairs.items():
+        back[i][r] = dsts[j][q]
+    for i in range(0, prob.n_src, src.tp):
+        assert np.array_equal(back[i], srcs[i])
+
+
+def test_text_rows_untouched():
+    rng = np.random.default_rng(42)
+    src, dst, tm = wl.random_layout_case(rng)
+    prob = oracle.Problem(src, dst, tm)
+    X = row_id_payload(tm.n_rows, tm.hidden)
+    srcs = brute_sources(src, tm, X)
+    pre = [rng.integers(0, 65536, size=(prob.dst_rows(), tm.hidden), dtype=np.uint16) for _ in range(prob.n_dst)]
+    dsts = [p.copy() for p in pre]
+    prob.forward(srcs, dsts)
+    for j in range(prob.n_dst):
+        sb, _ = prob.forward_map(j)
+        assert np.array_equal(dsts[j][sb < 0], pre[j][sb < 0])
+
+
+# ----------------------------------------------------------------------------
+# backward
+# ----------------------------------------------------------------------------
+
+def _f2b(x):
+    return wl.bf16_bits(torch.as_tensor(x, dtype=torch.float32).to(torch.bfloat16)).copy()
+
+
+def _b2f(bits):
+    return wl.bits_to_bf16(bits).to(torch.float32).numpy()
+
+
+@pytest.mark.parametrize("seed", range(15))
+def test_all_ones_gradient_returns_replica_count(seed):
+    rng = np.random.default_rng(3000 + seed)
+    src, dst, tm = wl.random_layout_case(rng)
+    prob = oracle.Problem(src, dst, tm)
+    g = [_f2b(np.ones((prob.dst_rows(), tm.hidden), np.float32)) for _ in range(prob.n_dst)]
+    sg = [np.full((r, tm.hidden), 0x7FC1, np.uint16) for r in prob.src_rows()]
+    prob.backward_bf16(g, sg)
+    for a in sg:
+        assert np.array_equal(_b2f(a), np.full(a.shape, float(dst.tp), np.float32))
+
+
+@pytest.mark.parametrize("seed", range(15))
+def test_backward_is_adjoint_of_forward(seed):
+    """<forward(x), g> over image rows == <x, backward(g)> with small-integer
+    values, for which every sum is exact in bf16/binary32."""
+    rng = np.random.default_rng(4000 + seed)
+    src, dst, tm = wl.random_layout_case(rng)
+    prob = oracle.Problem(src, dst, tm)
+    Xf = rng.integers(-8, 9, size=(tm.n_rows, tm.hidden)).astype(np.float32)
+    srcs = brute_sources(src, tm, _f2b(Xf))
+    dsts = [_f2b(np.zeros((prob.dst_rows(), tm.hidden), np.float32)) for _ in range(prob.n_dst)]
+    prob.forward(srcs, dsts)
+    gf = [rng.integers(-8, 9, size=(prob.dst_rows(), tm.hidden)).astype(np.float32) for _ in range(prob.n_dst)]
+    sg = [np.full((r, tm.hidden), 0x7FC1, np.uint16) for r in prob.src_rows()]
+    prob.backward_bf16([_f2b(x) for x in gf], sg)
+    lhs = 0.0
+    for j in range(prob.n_dst):
+        sb, _ = prob.forward_map(j)
+        lhs += float((_b2f(dsts[j]).astype(np.float64) * gf[j])[sb >= 0].sum())
+    rhs = sum(float((_b2f(srcs[i]).astype(np.float64) * _b2f(sg[i])).sum())
+              for i in range(0, prob.n_src, src.tp))
+    assert lhs == rhs
+    for i in range(0, prob.n_src, src.tp):                 # source TP replicas identical
+        for t in range(1, src.tp):
+            assert np.array_equal(sg[i], sg[i + t])
+
+
+def test_backward_tp1_is_inverse_permutation():
+    rng = np.random.default_rng(9)
+    from dataclasses import replace
+    for _ in range(10):
+        src, dst, tm = wl.random_layout_case(rng)
+        dst = replace(dst, tp=1)
+        X = row_id_payload(tm.n_rows, tm.hidden) & np.uint16(0x3FFF)   # finite bf16 patterns
+        prob, srcs, dsts = run_oracle_forward(src, dst, tm, X, text_value=0)
+        sg = [np.full(a.shape, 0x7FC1, np.uint16) for a in srcs]
+        prob.backward_bf16(dsts, sg)
+        for a, b in zip(sg, srcs):
+            assert np.array_equal(a, b)
+
+
+def test_backward_tp2_is_one_rounded_add():
+    """Two replicas: the fold is a single binary32 add (numpy float32) followed
+    by torch's bf16 rounding."""
+    rng = np.random.default_rng(10)
+    tm = wl.token_map_from_lens(rng, 1, 64, 32, [[5, 9, 17]])
+    src, dst = wl.Grid(dp=2), wl.Grid(tp=2, cp=2, cp_split=wl.CP_ZIGZAG)
+    prob = oracle.Problem(src, dst, tm)
+    scale = np.exp2(rng.integers(-20, 20, size=(prob.n_dst, prob.dst_rows(), 32))).astype(np.float32)
+    gf = rng.standard_normal((prob.n_dst, prob.dst_rows(), 32)).astype(np.float32) * scale
+    gb = [_f2b(gf[j]) for j in range(prob.n_dst)]
+    sg = [np.zeros((r, 32), np.uint16) for r in prob.src_rows()]
+    prob.backward_bf16(gb, sg)
+    # expected through the forward map and library arithmetic
+    for j in range(0, prob.n_dst, 2):
+        sb, sr = prob.forward_map(j)
+        s = (_b2f(gb[j]) + _b2f(gb[j + 1])).astype(np.float32)
+        want = _f2b(s)
+        for r in np.nonzero(sb >= 0)[0]:
+            assert np.array_equal(sg[sb[r]][sr[r]], want[r])
+
+
+def test_fixed_order_fold_and_rounding_fixture():
+    g = json.load(open(os.path.join(GOLDEN, "bf16_rounding.json")))
+    for case in g["round"]:
+        f = struct.unpack("<f", struct.pack("<I", int(case["f32_hex"], 16)))[0]
+        assert oracle.f32_to_bf16(f) == int(case["bf16_hex"], 16), case["why"]
+    for case in g["fold"]:
+        terms = case["terms"]
+        tp = len(terms)
+        tm = wl.TokenMap(1, 1, 1, [0], [0], [1])
+        prob = oracle.Problem(wl.Grid(), wl.Grid(tp=tp), tm)
+        grads = [_f2b([[t]]) for t in terms]
+        assert [float(_b2f(x)[0, 0]) for x in grads] == [float(t) for t in terms]   # representable
+        sg = [np.zeros((1, 1), np.uint16)]
+        prob.backward_bf16(grads, sg)
+        assert float(_b2f(sg[0])[0, 0]) == float(case["result"]), case["why"]
+
+
+def test_bf16_rounding_matches_torch_cast():
+    rng = np.random.default_rng(77)
+    bits = rng.integers(0, 2 ** 32, size=20000, dtype=np.uint64).astype(np.uint32)
+    f = bits.view(np.float32)
+    t = torch.from_numpy(f.copy()).to(torch.bfloat16)
+    want = wl.bf16_bits(t)
+    for x, w in zip(f.tolist()[:4000], want.tolist()[:4000]):
+        got = oracle.f32_to_bf16(x)
+        if x != x:
+            assert (got & 0x7F80) == 0x7F80 and (got & 0x7F) != 0      # NaN stays NaN
+        else:
+            assert got == w
+    for h in rng.integers(0, 65536, size=500).tolist():
+        v = oracle.bf16_to_f32(h)
+        w = wl.bits_to_bf16(np.array([h], np.uint16)).to(torch.float32).item()
+        assert (v != v and w != w) or v == w
+
+
+def test_backward_subnormals_are_kept():
+    """Two bf16 subnormals add to a binary32 subnormal that must not be flushed."""
+    tm = wl.TokenMap(1, 1, 1, [0], [0], [1])
+    prob = oracle.Problem(wl.Grid(), wl.Grid(tp=2), tm)
+    a = np.array([[0x0001]], np.uint16)      # smallest bf16 subnormal, 2^-133
+    b = np.array([[0x0002]], np.uint16)
+    sg = [np.zeros((1, 1), np.uint16)]
+    prob.backward_bf16([a, b], sg)
+    assert int(sg[0][0, 0]) == 0x0003
+
+
+def test_backward_ignores_text_rows_and_writes_every_source_row():
+    rng = np.random.default_rng(12)
+    for _ in range(10):
+        src, dst, tm = wl.random_layout_case(rng)
+        prob = oracle.Problem(src, dst, tm)
+        g = [_f2b(rng.integers(-4, 5, size=(prob.dst_rows(), tm.hidden)).astype(np.float32))
+             for _ in range(prob.n_dst)]
+        sg1 = [np.full((r, tm.hidden), 0x7FC1, np.uint16) for r in prob.src_rows()]
+        prob.backward_bf16(g, sg1)
+        assert all(not np.any(a == 0x7FC1) for a in sg1)             # every row overwritten
+        g2 = [x.copy() for x in g]
+        for j in range(prob.n_dst):
+            sb, _ = prob.forward_map(j)
+            g2[j][sb < 0] = 0x7FC0                                   # poison text-row grads
+        sg2 = [np.zeros((r, tm.hidden), np.uint16) for r in prob.src_rows()]
+        prob.backward_bf16(g2, sg2)
+        for a, b in zip(sg1, sg2):
+            assert np.array_equal(a, b)
+
+
+def test_named_workloads_have_the_stated_shapes():
+    w = wl.tiny()
+    assert (w.maps[0].batch, w.maps[0].seq, w.maps[0].hidden, w.maps[0].n_rows) == (2, 320, 64, 128)
+    w = wl.colocated4()
+    assert (w.maps[0].seq, w.maps[0].n_rows) == (16384, 32768)
+    w = wl.long_context()
+    m = w.maps[0]
+    assert m.seq == 131072 and m.hidden == 5120 and 0.30 * m.seq <= m.n_rows <= 0.30 * m.seq + 2304
+    assert 1 <= m.n_images <= 32 and m.img_len.min() >= 256 and m.img_len.max() <= 2304
+    w = wl.non_colocated()
+    assert len(w.maps) == 16 and all(4 <= x.n_images <= 16 and set(x.img_len) == {576} for x in w.maps)
+    w = wl.large_scale()
+    m = w.maps[0]
+    assert m.seq == 65536 and m.n_rows >= 32768 and m.img_len.min() >= 64 and m.img_len.max() <= 4096
+    for w in (wl.tiny(), wl.colocated4(), wl.long_context(), wl.large_scale()):
+        for m in w.maps:                                   # spans never overlap, stay in range
+            for b in range(m.batch):
+                sel = m.img_sample == b
+                s, l = m.img_start[sel].astype(np.int64), m.img_len[sel].astype(np.int64)
+                o = np.argsort(s)
+                assert np.all(s[o][1:] >= (s[o] + l[o])[:-1]) and np.all(s + l <= m.seq) and np.all(s >= 0)
