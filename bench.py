@@ -1,0 +1,240 @@
+#!/usr/bin/env python3
+"""Benchmark of the boundary layout transform on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input:
+hp_forward (source layout -> destination layout) followed by hp_backward
+(destination gradients -> source layout) on the long-context workload (vision
+DP8 -> LLM TP4 x CP8 zigzag, one 131072-token sample, hidden 5120, ~30 % image
+tokens).  All buffers are resident in HBM before the timed region.  The metric
+is effective HBM GB/s: algorithmic bytes of the two calls divided by their time.
+
+Prints ONE JSON line on stdout; progress goes to stderr.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import statistics
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+def read_traffic(workload: str):
+    """HBM bytes per launch measured with rocprofv3 counters, if a summary for
+    this workload has been committed under profiles/ (key = value lines)."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    out = {}
+    if os.path.exists(path):
+        for line in open(path):
+            if "=" in line and not line.lstrip().startswith("#"):
+                k, v = line.split("=", 1)
+                try:
+                    out[k.strip()] = float(v.split()[0])
+                except (ValueError, IndexError):
+                    pass
+    return out
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=15)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="long_context",
+                    choices=["tiny", "colocated4", "long_context", "non_colocated", "large_scale"])
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--tile-bytes", type=int, default=None)
+    ap.add_argument("--block-threads", type=int, default=None)
+    ap.add_argument("--nontemporal", type=int, default=None)
+    args = ap.parse_args()
+
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        log("bench.py: this build runs on ONE GPU: every source and destination rank is a buffer "
+            "in one GPU's HBM and there is no multi-GPU path. Re-run with --gpus 1.")
+        return 2
+
+    import torch
+    import paper_2605_27678_amd as hp
+    from paper_2605_27678_amd import workloads as wl
+
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible; the transform has no CPU path")
+        return 3
+    torch.cuda.set_device(0)
+    dev = "cuda:0"
+    for key, val in (("tile_bytes", args.tile_bytes), ("block_threads", args.block_threads),
+                     ("nontemporal", args.nontemporal)):
+        if val is not None:
+            hp.hp_set_option(key, val)
+
+    w = wl.CONFIGS[args.workload]()
+    maps = w.maps
+    H = maps[0].hidden
+    log(f"[bench] workload {w.name}: {len(maps)} microbatch(es), hidden {H}")
+
+    # ---- plans and resident buffers (one set per microbatch) ----
+    t0 = time.perf_counter()
+    plans = [hp.hp_plan_create(w.src, w.dst, m) for m in maps]
+    plan_ms = (time.perf_counter() - t0) * 1e3 / len(plans)
+    sets = []
+    for i, (p, m) in enumerate(zip(plans, maps)):
+        rows = p.src_rows()
+        src = [wl.random_bf16((r, H), w.seed * 100 + i * 7 + k, dev) for k, r in enumerate(rows)]
+        dst = [wl.random_bf16((p.info.dst_rows_per_buf, H), w.seed * 100 + 50 + j, dev)
+               for j in range(p.info.n_dst_bufs)]
+        grad = [wl.random_bf16((p.info.dst_rows_per_buf, H), w.seed * 100 + 90 + j, dev)
+                for j in range(p.info.n_dst_bufs)]
+        sgrad = [torch.zeros((r, H), dtype=torch.bfloat16, device=dev) for r in rows]
+        ps, pd = p.pointer_arrays(src, dst)
+        pgs, pgd = p.pointer_arrays(sgrad, grad)
+        sets.append(dict(plan=p, src=src, dst=dst, grad=grad, sgrad=sgrad, ps=ps, pd=pd, pgs=pgs, pgd=pgd))
+    fwd_bytes = sum(p.info.fwd_bytes for p in plans)
+    bwd_bytes = sum(p.info.bwd_bytes for p in plans)
+    boundary = sum(p.info.boundary_bytes for p in plans)
+    log(f"[bench] boundary {boundary / 1e6:.1f} MB, fwd {fwd_bytes / 1e9:.3f} GB, bwd {bwd_bytes / 1e9:.3f} GB, "
+        f"{sum(p.info.n_tiles for p in plans)} tiles, plan build {plan_ms:.2f} ms")
+
+    stream = torch.cuda.Stream()
+
+    def step(record=None):
+        if record is not None:
+            e = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+            e[0].record(stream)
+        for s in sets:
+            s["plan"].forward_raw(s["ps"], s["pd"], stream)
+        if record is not None:
+            e[1].record(stream)
+        for s in sets:
+            s["plan"].backward_raw(s["pgd"], s["pgs"], stream)
+        if record is not None:
+            e[2].record(stream)
+            record.append(e)
+
+    for _ in range(args.warmup):
+        step()
+    stream.synchronize()
+    torch.cuda.synchronize()
+    events = []
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step(events)
+    stream.synchronize()
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t0
+    fwd_ms = [e[0].elapsed_time(e[1]) for e in events]
+    bwd_ms = [e[1].elapsed_time(e[2]) for e in events]
+    ms_per_step = total_s * 1e3 / args.steps
+    value = (fwd_bytes + bwd_bytes) / (total_s / args.steps) / 1e9
+    f_avg, b_avg = statistics.fmean(fwd_ms), statistics.fmean(bwd_ms)
+    f_med, b_med = statistics.median(fwd_ms), statistics.median(bwd_ms)
+    log(f"[bench] fwd median {f_med:.4f} ms ({fwd_bytes / f_med / 1e6:.0f} GB/s), "
+        f"bwd median {b_med:.4f} ms ({bwd_bytes / b_med / 1e6:.0f} GB/s), step {ms_per_step:.4f} ms")
+
+    # ---- plain device copy of the same byte count: practical ceiling ----
+    n_copy = (fwd_bytes // 2) // 2
+    a = torch.empty(n_copy, dtype=torch.bfloat16, device=dev)
+    b = torch.empty_like(a)
+    with torch.cuda.stream(stream):
+        for _ in range(3):
+            b.copy_(a)
+        ce = [torch.cuda.Event(enable_timing=True) for _ in range(2)]
+        ce[0].record(stream)
+        for _ in range(10):
+            b.copy_(a)
+        ce[1].record(stream)
+    stream.synchronize()
+    copy_gbps = 10 * 2 * n_copy * 2 / (ce[0].elapsed_time(ce[1]) * 1e-3) / 1e9
+    del a, b
+    log(f"[bench] plain copy of {2 * n_copy * 2 / 1e9:.2f} GB traffic: {copy_gbps:.0f} GB/s")
+
+    # ---- roofline of the dominant (slower) kernel, durations from HIP events on its stream ----
+    n_launch = len(sets)
+    dominant = "hp_backward_kernel" if b_avg >= f_avg else "hp_forward_kernel"
+    dom_bytes = (bwd_bytes if dominant == "hp_backward_kernel" else fwd_bytes) / n_launch
+    dom_ms = (b_avg if dominant == "hp_backward_kernel" else f_avg) / n_launch
+    traffic = read_traffic(w.name)
+    tkey = "backward_bytes_per_launch" if dominant == "hp_backward_kernel" else "forward_bytes_per_launch"
+    roofline = {
+        "bound": "hbm", "kernel": dominant,
+        "achieved": dom_bytes / dom_ms / 1e6, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "frac": dom_bytes / dom_ms / 1e6 / HBM_PEAK_GBPS,
+        "traffic": traffic.get(tkey),
+        "algorithmic_bytes_per_launch": dom_bytes,
+        "avg_launch_ms": dom_ms,
+    }
+
+    # ---- the CPU oracle on the same workload, host cores of this machine ----
+    cpu_baseline = None
+    if not args.no_cpu_baseline:
+        from oracle import oracle
+        import numpy as np
+        log("[bench] timing the CPU oracle on the same workload (first microbatch) ...")
+        s, m = sets[0], maps[0]
+        prob = oracle.Problem(w.src, w.dst, m)
+        bits = lambda t: t.cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+        h_src = [bits(t) for t in s["src"]]
+        h_dst = [bits(t) for t in s["dst"]]
+        h_grad = [bits(t) for t in s["grad"]]
+        h_sg = [np.zeros((r, H), np.uint16) for r in s["plan"].src_rows()]
+        ncores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count()
+        ncores = min(ncores, int(os.environ.get("OMP_NUM_THREADS", ncores)))
+        res = {}
+        for nt in (ncores, 1):
+            oracle.set_threads(nt)
+            t0 = time.perf_counter()
+            prob.forward(h_src, h_dst)
+            t1 = time.perf_counter()
+            prob.backward_bf16(h_grad, h_sg)
+            t2 = time.perf_counter()
+            res[nt] = (t1 - t0, t2 - t1)
+            log(f"[bench] oracle {nt} thread(s): fwd {t1 - t0:.3f} s, bwd {t2 - t1:.3f} s")
+        p0 = s["plan"].info
+        ob = p0.fwd_bytes + p0.bwd_bytes
+        cpu_baseline = {
+            "value": ob / sum(res[ncores]) / 1e9, "unit": "GB/s", "cores": ncores, "kind": "oracle",
+            "sample": f"one full forward+backward pass of {w.name} (microbatch 0), {ob / 1e9:.2f} GB algorithmic",
+            "fwd_s": res[ncores][0], "bwd_s": res[ncores][1],
+            "one_thread_value": ob / sum(res[1]) / 1e9, "one_thread_fwd_s": res[1][0], "one_thread_bwd_s": res[1][1],
+        }
+        # the GPU result of the last step must equal what the oracle just computed
+        ok = all(np.array_equal(bits(t), h) for t, h in zip(s["sgrad"], h_sg))
+        cpu_baseline["gpu_matches_oracle"] = bool(ok)
+
+    out = {
+        "metric": "boundary fwd+bwd effective HBM GB/s and % of MI355X HBM peak, 1 GPU",
+        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "bf16 (backward accumulates in f32)", "data": "synthetic",
+        "config": {"workload": w.name, "src": f"tp{w.src.tp}dp{w.src.dp}",
+                   "dst": f"tp{w.dst.tp}cp{w.dst.cp}dp{w.dst.dp}",
+                   "batch": maps[0].batch, "seq": maps[0].seq, "hidden": H, "microbatches": len(maps),
+                   "image_rows": int(sum(m.n_rows for m in maps)), "boundary_bytes": boundary,
+                   "tile_bytes": hp.hp_get_option("tile_bytes"),
+                   "block_threads": hp.hp_get_option("block_threads"),
+                   "nontemporal": hp.hp_get_option("nontemporal")},
+        "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
+        "forward": {"bytes": fwd_bytes, "median_ms": f_med, "min_ms": min(fwd_ms), "max_ms": max(fwd_ms),
+                    "GBps": fwd_bytes / f_med / 1e6, "pct_of_hbm_peak": fwd_bytes / f_med / 1e6 / HBM_PEAK_GBPS * 100},
+        "backward": {"bytes": bwd_bytes, "median_ms": b_med, "min_ms": min(bwd_ms), "max_ms": max(bwd_ms),
+                     "GBps": bwd_bytes / b_med / 1e6, "pct_of_hbm_peak": bwd_bytes / b_med / 1e6 / HBM_PEAK_GBPS * 100},
+        "plan_build_ms": plan_ms,
+        "device_copy_GBps": copy_gbps,
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+    }
+    print(json.dumps(out), flush=True)
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

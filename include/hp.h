@@ -1,0 +1,232 @@
+/*
+ * hp.h - C ABI of the heterogeneous-parallelism boundary layout transform for
+ * AMD MI355X (gfx950).
+ *
+ * The operation (paper, Method section, paragraph on boundary edges): an edge
+ * u -> v between two modules carries ONE tensor with TWO distributed
+ * representations, one under the source module's grid G_u on ranks R_u and one
+ * under the destination module's grid G_v on ranks R_v.  Forward materialises
+ * the activation in the destination layout; backward applies the matching
+ * reverse transform so that gradients return to the source layout.  Here u is a
+ * vision encoder (TP x DP grid, CP = 1) and v is the language model
+ * (TP x CP x DP grid): the encoder's projected tokens are inserted into the
+ * fused multimodal sequence at the image-token positions (Fig. 1 caption;
+ * appendix "Pipeline schedule details", phase 2), the fused sequence is split
+ * over the CP ranks (Introduction: CP shards the fused language sequence) and
+ * the result is present on every TP rank of the receiving group
+ * (Non-colocated communicator: local TP/CP broadcast to non-leader ranks).
+ *
+ * Every rank is emulated as its own buffer in one GPU's HBM.  The library moves
+ * rows between those buffers with hand-written gfx950 kernels; it performs no
+ * inter-GPU communication.
+ *
+ * Conventions (the paper leaves them open; they are fixed here):
+ *   - Rank order inside a grid: tp fastest, then cp, then dp.  Buffer index of a
+ *     source rank: tp + TP_src*dp.  Buffer index of a destination rank:
+ *     tp + TP_dst*(cp + CP_dst*dp).  rank_offset only names the physical ranks
+ *     (overlapping ranges = colocated, disjoint = non-colocated; appendix
+ *     "Open-source user configuration example"); it does not change the result.
+ *   - A source buffer is [rows, hidden]: the tokens of the images assigned to
+ *     that dp rank, concatenated in global image order.  All TP ranks of one
+ *     source dp rank hold identical copies; forward reads copy tp = 0 (the
+ *     boundary leader), backward writes every copy.
+ *   - Image -> source dp rank: the map's img_src_dp if given, else contiguous
+ *     balanced intervals of the K images: rank d holds images
+ *     [floor(d*K/DP), floor((d+1)*K/DP)).  With a constant number of images per
+ *     sample this is the paper's equal batch intervals (Method: logical
+ *     batch-shard transform).  Fan-in, fan-out and equal-DP all follow from it.
+ *   - Sample b lives on destination dp rank b / (batch/DP_dst).
+ *   - A destination buffer is [B_local, S_local, hidden] (HP_ROW_BSH) or
+ *     [S_local, B_local, hidden] (HP_ROW_SBH), densely packed.
+ *   - Backward SUMS the TP replicas of a row (the adjoint of replication):
+ *     binary32 left fold in ascending tp order, round-to-nearest-even,
+ *     subnormals kept, then one rounding to bf16.  (The paper's own stack
+ *     returns the leader's copy without a reduction.)
+ *
+ * Threading / ownership: a plan is immutable after creation and may be used
+ * from several host threads and streams at once.  The caller owns every
+ * activation and gradient buffer and the stream; the plan owns only its device
+ * tables.  hp_forward / hp_backward enqueue work on the caller's stream and
+ * return without synchronising; they allocate nothing.  Buffers must stay valid
+ * until the stream has passed the call.
+ *
+ * Errors: every int-returning call returns HP_OK (0) or a negative HP_E* code;
+ * nothing throws or aborts across this boundary and output arguments are left
+ * untouched on failure.
+ */
+#ifndef HP_H_
+#define HP_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define HP_OK        0
+#define HP_EINVAL   (-1)  /* null pointer, non-positive size, unknown enum value            */
+#define HP_ELAYOUT  (-2)  /* grids and token map do not divide / exceed a stated limit      */
+#define HP_EMAP     (-3)  /* bad image spans: out of range, overlapping, unordered samples  */
+#define HP_ENOMEM   (-4)  /* host or device allocation failed                               */
+#define HP_EHIP     (-5)  /* a HIP runtime call failed (see hp_last_hip_error)              */
+#define HP_ESTATE   (-6)  /* plan has no device tables (host-only plan) or wrong device     */
+#define HP_EALIGN   (-7)  /* a buffer pointer is not aligned to the element size            */
+
+/* hp_layout_t.tp_mode (destination only) */
+#define HP_TP_REPLICATE  0   /* every TP rank holds the full CP-local sequence               */
+#define HP_TP_SEQ_SHARD  1   /* sequence parallelism: TP rank t holds the t-th of TP equal
+                                contiguous pieces of the CP-local sequence; no replication  */
+/* hp_layout_t.cp_split (destination only) */
+#define HP_CP_CONTIGUOUS 0   /* cp rank r holds positions [r*S/C, (r+1)*S/C)                 */
+#define HP_CP_ZIGZAG     1   /* load-balanced: 2C equal chunks, rank r holds chunk r followed
+                                by chunk 2C-1-r                                              */
+/* hp_layout_t.row_order (destination only) */
+#define HP_ROW_BSH 0
+#define HP_ROW_SBH 1
+/* hp_token_map_t.dtype */
+#define HP_BF16 0
+
+#define HP_MAX_BUFFERS 224   /* source + destination buffers of one plan                     */
+#define HP_MAX_TP      16    /* replicas summed by hp_backward                               */
+
+/* One module's logical grid G_m and the first id of its physical rank range R_m
+ * (Method, first paragraph; appendix "Open-source user configuration example").
+ * pp is accepted for completeness and must be >= 1: only the boundary stage
+ * (source's last stage, destination's first stage) takes part.  For the source
+ * grid cp must be 1 and tp_mode/cp_split/row_order must be 0. */
+typedef struct hp_layout {
+    int32_t tp, cp, dp, pp;
+    int32_t rank_offset;
+    int32_t tp_mode;
+    int32_t cp_split;
+    int32_t row_order;
+} hp_layout_t;
+
+/* Shape of the fused sequence and where the image tokens sit in it.  All
+ * pointers are HOST arrays of n_images entries, read during plan creation only.
+ * Images are listed in global order: img_sample non-decreasing; within a sample
+ * any non-overlapping placement.  Image k occupies positions
+ * [img_start[k], img_start[k]+img_len[k]) of sample img_sample[k].
+ * img_src_dp may be NULL (balanced rule above) or a non-decreasing array of
+ * source dp ranks. */
+typedef struct hp_token_map {
+    int32_t batch, seq, hidden;
+    int32_t dtype;                 /* HP_BF16 */
+    int32_t n_images;
+    const int32_t *img_sample;
+    const int32_t *img_start;
+    const int32_t *img_len;
+    const int32_t *img_src_dp;
+} hp_token_map_t;
+
+typedef struct hp_plan hp_plan_t;
+
+typedef struct hp_plan_info {
+    int32_t n_src_bufs;        /* TP_src * DP_src                                             */
+    int32_t n_dst_bufs;        /* TP_dst * CP_dst * DP_dst                                    */
+    int32_t src_copies;        /* TP_src: identical copies of every source row                */
+    int32_t dst_copies;        /* TP_dst when replicated, 1 when sequence-sharded             */
+    int64_t n_rows;            /* N: image-token rows of the boundary tensor                  */
+    int64_t row_bytes;         /* hidden * element size                                       */
+    int64_t dst_rows_per_buf;  /* rows of every destination buffer                            */
+    int64_t boundary_bytes;    /* N * row_bytes                                               */
+    int64_t fwd_bytes;         /* algorithmic traffic of hp_forward: (1 + dst_copies)*boundary */
+    int64_t bwd_bytes;         /* of hp_backward: (dst_copies + src_copies)*boundary          */
+    int32_t n_segments;        /* runs contiguous on both sides                               */
+    int32_t n_tiles;           /* work items = workgroups per launch                          */
+    int32_t on_device;         /* 1 if device tables exist                                    */
+    int32_t device;            /* HIP device ordinal of the tables, -1 if none                */
+} hp_plan_info_t;
+
+/* A maximal run of image-token rows that is contiguous in the source buffer and
+ * evenly strided in the destination buffer(s). */
+typedef struct hp_segment {
+    int32_t src_buf;           /* source buffer index of copy tp = 0                          */
+    int32_t dst_buf0;          /* first destination buffer; copies are dst_buf0 .. +dst_copies-1 */
+    int64_t src_row0;
+    int64_t dst_row0;
+    int64_t n_rows;
+    int64_t dst_row_stride;    /* 1 for HP_ROW_BSH, B_local for HP_ROW_SBH                    */
+} hp_segment_t;
+
+/* hp_plan_create - the paper's "derive every rank's source coordinate,
+ * destination coordinate and batch interval" step (Colocated communicator,
+ * second paragraph; both sides build the same static routing pattern,
+ * Non-colocated communicator): validates the two grids and the token map,
+ * builds the per-segment and per-tile gather/scatter tables on the host and
+ * uploads them to the CURRENT HIP device (one synchronous allocation + copy).
+ * src, dst, map: host structs, read only during the call.
+ * *out receives an owned plan; release it with hp_plan_destroy. */
+int hp_plan_create(const hp_layout_t *src, const hp_layout_t *dst,
+                   const hp_token_map_t *map, hp_plan_t **out);
+
+/* Same, but makes no HIP call: the plan can be queried and its segments read,
+ * hp_forward / hp_backward on it return HP_ESTATE. */
+int hp_plan_create_host(const hp_layout_t *src, const hp_layout_t *dst,
+                        const hp_token_map_t *map, hp_plan_t **out);
+
+/* Frees host and device tables.  NULL is allowed.  The caller must have
+ * synchronised every stream that still uses the plan. */
+void hp_plan_destroy(hp_plan_t *plan);
+
+int hp_plan_query(const hp_plan_t *plan, hp_plan_info_t *info);
+
+/* rows[i] = rows of source buffer i (i = tp + TP_src*dp).  `cap` = entries
+ * available in `rows` (host array); returns the number of source buffers, or a
+ * negative error.  Empty source ranks have 0 rows. */
+int hp_plan_src_rows(const hp_plan_t *plan, int64_t *rows, int32_t cap);
+
+/* Copies up to `cap` segments into `out` (host array); returns the total
+ * number of segments. */
+int hp_plan_segments(const hp_plan_t *plan, hp_segment_t *out, int32_t cap);
+
+/* hp_forward - materialise the source activation in the destination layout
+ * (Method: "forward materializes the activation in the destination layout";
+ * fan-in concatenation in batch order, Non-colocated communicator; insertion
+ * into the text embeddings, "Pipeline schedule details" phase 2).
+ *   src_bufs: HOST array of n_src_bufs DEVICE pointers, index tp + TP_src*dp,
+ *             each [rows_i, hidden] bf16.  Only copies with tp == 0 are read;
+ *             entries of other copies and of empty ranks may be NULL.
+ *   dst_bufs: HOST array of n_dst_bufs DEVICE pointers, index
+ *             tp + TP_dst*(cp + CP_dst*dp), each [dst_rows_per_buf, hidden].
+ *             Exactly the image-token rows are written; all other bytes (the
+ *             text embeddings the caller placed there) are left as found.
+ *   stream:   a hipStream_t (NULL = the default stream).
+ * Pointers must be aligned to 2 bytes; 16-byte alignment selects the vector
+ * path.  Returns after enqueueing. */
+int hp_forward(const hp_plan_t *plan, const void *const *src_bufs,
+               void *const *dst_bufs, void *stream);
+
+/* hp_backward - route destination-layout gradients back to the source layout
+ * (Method: "backward applies the matching reverse layout transform"; fan-in
+ * backward splits along the recorded intervals; the result is placed on every
+ * TP rank of the source side, Non-colocated communicator, backward paragraph).
+ * The dst_copies replicas of each image-token row are summed in binary32 in
+ * ascending tp order and rounded once to bf16.
+ *   dst_grad_bufs: HOST array of n_dst_bufs DEVICE pointers, same shapes as
+ *                  hp_forward's dst_bufs; only image-token rows are read.
+ *   src_grad_bufs: HOST array of n_src_bufs DEVICE pointers; every row of
+ *                  every buffer is overwritten (all TP copies get the same
+ *                  values).  Entries of empty ranks may be NULL.
+ */
+int hp_backward(const hp_plan_t *plan, const void *const *dst_grad_bufs,
+                void *const *src_grad_bufs, void *stream);
+
+/* Process-wide tuning knobs (integers).  Known keys:
+ *   "tile_bytes"    bytes of boundary data per workgroup (plans created later)
+ *   "block_threads" workgroup size, multiple of 64 in [64, 1024]
+ *   "nontemporal"   1 = streaming (non-temporal) loads and stores
+ * Returns HP_EINVAL for an unknown key or an out-of-range value. */
+int hp_set_option(const char *key, int64_t value);
+int64_t hp_get_option(const char *key);     /* INT64_MIN for an unknown key */
+
+const char *hp_strerror(int code);
+/* hipError_t value of the most recent failing HIP call on this thread (0 if none). */
+int hp_last_hip_error(void);
+const char *hp_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* HP_H_ */

@@ -1,0 +1,9 @@
+"""MI355X-native boundary layout transform (forward materialise / backward
+route) of heterogeneous-parallel multimodal training: a C-ABI library of HIP
+kernels (libhp.so) plus this thin binding."""
+from .binding import (HpError, Plan, hp_backward, hp_forward, hp_get_option, hp_plan_create,
+                      hp_plan_create_host, hp_set_option, hp_version)
+from .workloads import Grid, TokenMap
+
+__all__ = ["Grid", "TokenMap", "Plan", "HpError", "hp_plan_create", "hp_plan_create_host",
+           "hp_forward", "hp_backward", "hp_set_option", "hp_get_option", "hp_version"]

@@ -1,0 +1,237 @@
+"""ctypes binding of libhp.so - argument marshalling only.
+
+Function names mirror the C ABI in include/hp.h (hp_plan_create, hp_forward,
+hp_backward, ...).  Every step of the transform runs in the library's HIP
+kernels; there is no Python or CPU fallback: if the library has not been built
+or cannot be loaded, every entry point raises.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import List, Optional, Sequence
+
+import numpy as np
+
+from .workloads import Grid, TokenMap
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_PKG, "libhp.so")
+
+HP_OK = 0
+HP_EINVAL, HP_ELAYOUT, HP_EMAP, HP_ENOMEM, HP_EHIP, HP_ESTATE, HP_EALIGN = -1, -2, -3, -4, -5, -6, -7
+
+
+class HpError(RuntimeError):
+    def __init__(self, code: int, what: str):
+        self.code = code
+        msg = _lib().hp_strerror(code).decode()
+        if code == HP_EHIP:
+            msg += f" (hipError {_lib().hp_last_hip_error()})"
+        super().__init__(f"{what}: {msg} [{code}]")
+
+
+class hp_layout_t(C.Structure):
+    _fields_ = [("tp", C.c_int32), ("cp", C.c_int32), ("dp", C.c_int32), ("pp", C.c_int32),
+                ("rank_offset", C.c_int32), ("tp_mode", C.c_int32), ("cp_split", C.c_int32),
+                ("row_order", C.c_int32)]
+
+
+class hp_token_map_t(C.Structure):
+    _fields_ = [("batch", C.c_int32), ("seq", C.c_int32), ("hidden", C.c_int32),
+                ("dtype", C.c_int32), ("n_images", C.c_int32),
+                ("img_sample", C.POINTER(C.c_int32)), ("img_start", C.POINTER(C.c_int32)),
+                ("img_len", C.POINTER(C.c_int32)), ("img_src_dp", C.POINTER(C.c_int32))]
+
+
+class hp_plan_info_t(C.Structure):
+    _fields_ = [("n_src_bufs", C.c_int32), ("n_dst_bufs", C.c_int32),
+                ("src_copies", C.c_int32), ("dst_copies", C.c_int32),
+                ("n_rows", C.c_int64), ("row_bytes", C.c_int64), ("dst_rows_per_buf", C.c_int64),
+                ("boundary_bytes", C.c_int64), ("fwd_bytes", C.c_int64), ("bwd_bytes", C.c_int64),
+                ("n_segments", C.c_int32), ("n_tiles", C.c_int32),
+                ("on_device", C.c_int32), ("device", C.c_int32)]
+
+
+class hp_segment_t(C.Structure):
+    _fields_ = [("src_buf", C.c_int32), ("dst_buf0", C.c_int32), ("src_row0", C.c_int64),
+                ("dst_row0", C.c_int64), ("n_rows", C.c_int64), ("dst_row_stride", C.c_int64)]
+
+
+EXPORTS = ["hp_plan_create", "hp_plan_create_host", "hp_plan_destroy", "hp_plan_query",
+           "hp_plan_src_rows", "hp_plan_segments", "hp_forward", "hp_backward",
+           "hp_set_option", "hp_get_option", "hp_strerror", "hp_last_hip_error", "hp_version"]
+
+_handle = None
+
+
+def _lib():
+    """Loads libhp.so once.  Raises if it is missing: there is no fallback."""
+    global _handle
+    if _handle is not None:
+        return _handle
+    if not os.path.exists(LIB_PATH):
+        raise RuntimeError(
+            f"{LIB_PATH} is missing: build it first (python -m paper_2605_27678_amd.build or "
+            "__graft_entry__.build()); the transform has no CPU or PyTorch fallback")
+    L = C.CDLL(LIB_PATH)
+    vp, i32, i64 = C.c_void_p, C.c_int32, C.c_int64
+    L.hp_plan_create.argtypes = [C.POINTER(hp_layout_t), C.POINTER(hp_layout_t),
+                                 C.POINTER(hp_token_map_t), C.POINTER(vp)]
+    L.hp_plan_create_host.argtypes = L.hp_plan_create.argtypes
+    L.hp_plan_destroy.argtypes = [vp]
+    L.hp_plan_destroy.restype = None
+    L.hp_plan_query.argtypes = [vp, C.POINTER(hp_plan_info_t)]
+    L.hp_plan_src_rows.argtypes = [vp, C.POINTER(i64), i32]
+    L.hp_plan_segments.argtypes = [vp, C.POINTER(hp_segment_t), i32]
+    L.hp_forward.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp]
+    L.hp_backward.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp]
+    L.hp_set_option.argtypes = [C.c_char_p, i64]
+    L.hp_get_option.argtypes = [C.c_char_p]
+    L.hp_get_option.restype = i64
+    L.hp_strerror.argtypes = [C.c_int]
+    L.hp_strerror.restype = C.c_char_p
+    L.hp_version.restype = C.c_char_p
+    for f in ("hp_plan_create", "hp_plan_create_host", "hp_plan_query", "hp_plan_src_rows",
+              "hp_plan_segments", "hp_forward", "hp_backward", "hp_set_option", "hp_last_hip_error"):
+        getattr(L, f).restype = C.c_int
+    _handle = L
+    return L
+
+
+def _check(rc: int, what: str) -> int:
+    if rc < 0:
+        raise HpError(rc, what)
+    return rc
+
+
+def _layout(g: Grid) -> hp_layout_t:
+    return hp_layout_t(g.tp, g.cp, g.dp, g.pp, g.rank_offset, g.tp_mode, g.cp_split, g.row_order)
+
+
+def _i32p(a: Optional[np.ndarray]):
+    return C.POINTER(C.c_int32)() if a is None else a.ctypes.data_as(C.POINTER(C.c_int32))
+
+
+def _token_map(m: TokenMap):
+    keep = [np.ascontiguousarray(x, dtype=np.int32) for x in (m.img_sample, m.img_start, m.img_len)]
+    dp = None if m.img_src_dp is None else np.ascontiguousarray(m.img_src_dp, dtype=np.int32)
+    t = hp_token_map_t(m.batch, m.seq, m.hidden, 0, m.n_images,
+                       _i32p(keep[0]), _i32p(keep[1]), _i32p(keep[2]), _i32p(dp))
+    return t, (keep, dp)
+
+
+def hp_set_option(key: str, value: int) -> None:
+    _check(_lib().hp_set_option(key.encode(), int(value)), f"hp_set_option({key})")
+
+
+def hp_get_option(key: str) -> int:
+    return int(_lib().hp_get_option(key.encode()))
+
+
+def hp_version() -> str:
+    return _lib().hp_version().decode()
+
+
+def _stream_handle(stream) -> C.c_void_p:
+    if stream is None:
+        return C.c_void_p(0)
+    if hasattr(stream, "cuda_stream"):
+        return C.c_void_p(int(stream.cuda_stream))
+    return C.c_void_p(int(stream))
+
+
+class Plan:
+    """Owns one hp_plan_t.  `host_only=True` builds the tables without touching
+    the GPU (for inspection on machines without one)."""
+
+    def __init__(self, src: Grid, dst: Grid, tmap: TokenMap, host_only: bool = False):
+        L = _lib()
+        self._h = C.c_void_p(0)
+        tm, keep = _token_map(tmap)
+        fn = L.hp_plan_create_host if host_only else L.hp_plan_create
+        _check(fn(C.byref(_layout(src)), C.byref(_layout(dst)), C.byref(tm), C.byref(self._h)),
+               "hp_plan_create")
+        del keep
+        self.info = hp_plan_info_t()
+        _check(L.hp_plan_query(self._h, C.byref(self.info)), "hp_plan_query")
+        self.hidden = tmap.hidden
+
+    # -- introspection ------------------------------------------------------
+    def src_rows(self) -> List[int]:
+        n = self.info.n_src_bufs
+        buf = (C.c_int64 * n)()
+        _check(_lib().hp_plan_src_rows(self._h, buf, n), "hp_plan_src_rows")
+        return list(buf)
+
+    def segments(self) -> List[hp_segment_t]:
+        n = self.info.n_segments
+        arr = (hp_segment_t * max(n, 1))()
+        _check(_lib().hp_plan_segments(self._h, arr, n), "hp_plan_segments")
+        return [arr[i] for i in range(n)]
+
+    # -- marshalling --------------------------------------------------------
+    def _pointers(self, tensors: Sequence, rows: Sequence[int], what: str):
+        P = (C.c_void_p * len(tensors))()
+        for i, (t, r) in enumerate(zip(tensors, rows)):
+            if t is None:
+                P[i] = None
+                continue
+            if not t.is_cuda or not t.is_contiguous() or t.element_size() != 2:
+                raise ValueError(f"{what}[{i}]: need a contiguous 2-byte CUDA tensor")
+            if t.numel() < r * self.hidden:
+                raise ValueError(f"{what}[{i}]: {t.numel()} elements, plan needs {r * self.hidden}")
+            P[i] = t.data_ptr() if t.numel() else None
+        return P
+
+    def _src_dst(self, src_bufs, dst_bufs):
+        if len(src_bufs) != self.info.n_src_bufs or len(dst_bufs) != self.info.n_dst_bufs:
+            raise ValueError("wrong number of buffers for this plan")
+        ps = self._pointers(src_bufs, self.src_rows(), "src")
+        pd = self._pointers(dst_bufs, [self.info.dst_rows_per_buf] * len(dst_bufs), "dst")
+        return ps, pd
+
+    def forward(self, src_bufs: Sequence, dst_bufs: Sequence, stream=None) -> None:
+        ps, pd = self._src_dst(src_bufs, dst_bufs)
+        _check(_lib().hp_forward(self._h, ps, pd, _stream_handle(stream)), "hp_forward")
+
+    def backward(self, dst_grad_bufs: Sequence, src_grad_bufs: Sequence, stream=None) -> None:
+        ps, pd = self._src_dst(src_grad_bufs, dst_grad_bufs)
+        _check(_lib().hp_backward(self._h, pd, ps, _stream_handle(stream)), "hp_backward")
+
+    # raw-pointer variants for timing loops (pointer arrays prepared once)
+    def pointer_arrays(self, src_bufs: Sequence, dst_bufs: Sequence):
+        return self._src_dst(src_bufs, dst_bufs)
+
+    def forward_raw(self, ps, pd, stream=None) -> None:
+        _check(_lib().hp_forward(self._h, ps, pd, _stream_handle(stream)), "hp_forward")
+
+    def backward_raw(self, pd, ps, stream=None) -> None:
+        _check(_lib().hp_backward(self._h, pd, ps, _stream_handle(stream)), "hp_backward")
+
+    def close(self) -> None:
+        if self._h:
+            _lib().hp_plan_destroy(self._h)
+            self._h = C.c_void_p(0)
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+
+def hp_plan_create(src: Grid, dst: Grid, tmap: TokenMap) -> Plan:
+    return Plan(src, dst, tmap)
+
+
+def hp_plan_create_host(src: Grid, dst: Grid, tmap: TokenMap) -> Plan:
+    return Plan(src, dst, tmap, host_only=True)
+
+
+def hp_forward(plan: Plan, src_bufs, dst_bufs, stream=None) -> None:
+    plan.forward(src_bufs, dst_bufs, stream)
+
+
+def hp_backward(plan: Plan, dst_grad_bufs, src_grad_bufs, stream=None) -> None:
+    plan.backward(dst_grad_bufs, src_grad_bufs, stream)

@@ -1,0 +1,92 @@
+"""Shared driver of the GPU parity tests: same seeded inputs through the HIP
+library (via its C ABI) and through the CPU oracle, compared element by
+element as raw 16-bit patterns."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import paper_2605_27678_amd as hp
+from oracle import oracle
+from paper_2605_27678_amd import workloads as wl
+
+SENTINEL_GPU = 0x7FC5      # bf16 NaN patterns no computation here produces
+SENTINEL_CPU = 0x7FC9
+
+
+def _bits_cpu(t: torch.Tensor) -> np.ndarray:
+    return t.contiguous().view(torch.int16).numpy().view(np.uint16)
+
+
+def _to_host_bits(t: torch.Tensor) -> np.ndarray:
+    return _bits_cpu(t.cpu())
+
+
+def make_inputs(prob: oracle.Problem, seed: int, gen_device: str):
+    """Source activations (TP copies other than 0 hold different data on
+    purpose: forward must read the leader copy only), destination prefill
+    ("text embeddings") and destination gradients (every replica different)."""
+    H = prob.hidden
+    rows = prob.src_rows()
+    tp = prob.src_grid.tp
+    src = []
+    for i, r in enumerate(rows):
+        s = seed * 1000 + i                                  # distinct per copy
+        src.append(wl.random_bf16((r, H), s, gen_device))
+    dst_rows = prob.dst_rows()
+    pre = [wl.random_bf16((dst_rows, H), seed * 1000 + 300 + j, gen_device) for j in range(prob.n_dst)]
+    grads = [wl.random_bf16((dst_rows, H), seed * 1000 + 600 + j, gen_device) for j in range(prob.n_dst)]
+    return src, pre, grads
+
+
+def check_case(src_grid, dst_grid, tm, seed=1, gen_device="cpu", stream=None, check_backward=True,
+               grads_override=None):
+    """Runs forward and backward on both sides and asserts bit equality.
+    Returns the plan info."""
+    dev = "cuda:0"
+    plan = hp.hp_plan_create(src_grid, dst_grid, tm)
+    prob = oracle.Problem(src_grid, dst_grid, tm)
+    assert plan.src_rows() == prob.src_rows()
+    assert plan.info.dst_rows_per_buf == prob.dst_rows()
+    src, pre, grads = make_inputs(prob, seed, gen_device)
+    if grads_override is not None:
+        grads = grads_override
+    st = stream if stream is not None else torch.cuda.current_stream()
+
+    # ---- forward ----
+    g_src = [t.to(dev) for t in src]
+    g_dst = [t.to(dev).clone() for t in pre]
+    torch.cuda.synchronize()
+    hp.hp_forward(plan, g_src, g_dst, st)
+    torch.cuda.synchronize()
+    h_src = [_to_host_bits(t) for t in src]
+    o_dst = [_to_host_bits(t).copy() for t in pre]
+    prob.forward(h_src, o_dst)
+    for j in range(prob.n_dst):
+        got = _to_host_bits(g_dst[j])
+        assert np.array_equal(got, o_dst[j]), f"forward mismatch in destination buffer {j}"
+    del g_dst, o_dst, pre
+
+    # ---- backward ----
+    if check_backward:
+        g_grads = [t.to(dev) for t in grads]
+        g_sg = [torch.full((r, prob.hidden), 0, dtype=torch.int16, device=dev).fill_(SENTINEL_GPU).view(torch.bfloat16)
+                for r in prob.src_rows()]
+        torch.cuda.synchronize()
+        hp.hp_backward(plan, g_grads, g_sg, st)
+        torch.cuda.synchronize()
+        h_grads = [_to_host_bits(t) for t in grads]
+        o_sg = [np.full((r, prob.hidden), SENTINEL_CPU, np.uint16) for r in prob.src_rows()]
+        prob.backward_bf16(h_grads, o_sg)
+        for i in range(prob.n_src):
+            got = _to_host_bits(g_sg[i])
+            if not np.array_equal(got, o_sg[i]):
+                # NaN results may differ in payload only
+                a_nan = ((got & 0x7F80) == 0x7F80) & ((got & 0x7F) != 0)
+                b_nan = ((o_sg[i] & 0x7F80) == 0x7F80) & ((o_sg[i] & 0x7F) != 0)
+                same = (got == o_sg[i]) | (a_nan & b_nan)
+                assert same.all(), f"backward mismatch in source buffer {i}"
+                assert not np.any(got == SENTINEL_GPU), f"source buffer {i} has unwritten rows"
+    info = plan.info
+    plan.close()
+    return info

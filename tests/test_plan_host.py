@@ -1,0 +1,154 @@
+"""Host logic of the library, no GPU needed: the C ABI loads and exports what
+include/hp.h declares, the plan builder's segment tables describe exactly the
+row routing the oracle derives, and bad inputs come back as error codes."""
+import ctypes as C
+import os
+import re
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+import paper_2605_27678_amd as hp
+from oracle import oracle
+from paper_2605_27678_amd import binding
+from paper_2605_27678_amd import workloads as wl
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    text = open(os.path.join(ROOT, "include", "hp.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    declared = set(re.findall(r"\b(hp_[a-z_0-9]+)\s*\(", text))
+    assert {"hp_plan_create", "hp_forward", "hp_backward", "hp_plan_destroy"} <= declared
+    L = C.CDLL(binding.LIB_PATH)
+    for name in sorted(declared):
+        assert hasattr(L, name), name
+    assert declared == set(binding.EXPORTS)
+    assert "gfx950" in hp.hp_version()
+
+
+def expand_segments(plan):
+    """Per destination buffer: (src_buf, src_row) of every local row, -1 = text."""
+    info = plan.info
+    sb = -np.ones((info.n_dst_bufs, info.dst_rows_per_buf), np.int32)
+    sr = -np.ones((info.n_dst_bufs, info.dst_rows_per_buf), np.int64)
+    for s in plan.segments():
+        rows = s.dst_row0 + s.dst_row_stride * np.arange(s.n_rows)
+        for c in range(info.dst_copies):
+            assert np.all(sb[s.dst_buf0 + c, rows] == -1)          # no row written twice
+            sb[s.dst_buf0 + c, rows] = s.src_buf
+            sr[s.dst_buf0 + c, rows] = s.src_row0 + np.arange(s.n_rows)
+    return sb, sr
+
+
+def check_against_oracle(src, dst, tm):
+    plan = hp.hp_plan_create_host(src, dst, tm)
+    prob = oracle.Problem(src, dst, tm)
+    info = plan.info
+    assert info.n_src_bufs == prob.n_src and info.n_dst_bufs == prob.n_dst
+    assert plan.src_rows() == prob.src_rows()
+    assert info.dst_rows_per_buf == prob.dst_rows()
+    assert info.n_rows == tm.n_rows and info.row_bytes == 2 * tm.hidden
+    assert info.boundary_bytes == tm.n_rows * tm.hidden * 2
+    assert info.fwd_bytes == (1 + info.dst_copies) * info.boundary_bytes
+    assert info.bwd_bytes == (info.dst_copies + info.src_copies) * info.boundary_bytes
+    sb, sr = expand_segments(plan)
+    for j in range(prob.n_dst):
+        osb, osr = prob.forward_map(j)
+        assert np.array_equal(sb[j], osb), j
+        assert np.array_equal(sr[j], osr), j
+    plan.close()
+    return info
+
+
+@pytest.mark.parametrize("seed", range(80))
+def test_segments_match_oracle_walk_random_layouts(seed):
+    rng = np.random.default_rng(seed)
+    src, dst, tm = wl.random_layout_case(rng)
+    check_against_oracle(src, dst, tm)
+    if (tm.seq // dst.cp) % dst.tp == 0:
+        check_against_oracle(src, replace(dst, tp_mode=wl.TP_SEQ_SHARD), tm)
+
+
+@pytest.mark.parametrize("name", ["tiny", "colocated4", "long_context", "large_scale"])
+def test_segments_match_oracle_walk_named_configs(name):
+    w = wl.scaled(wl.CONFIGS[name](), 8)           # same spans and grids, small hidden
+    info = check_against_oracle(w.src, w.dst, w.maps[0])
+    assert 1 <= info.n_segments <= 3 * w.maps[0].n_images
+
+
+def test_non_colocated_microbatches_and_contiguous_variant():
+    w = wl.scaled(wl.non_colocated(n_microbatches=4), 8)
+    for tm in w.maps:
+        check_against_oracle(w.src, w.dst, tm)
+        check_against_oracle(w.src, replace(w.dst, cp_split=wl.CP_CONTIGUOUS), tm)
+
+
+def test_full_size_infos():
+    w = wl.long_context()
+    p = hp.hp_plan_create_host(w.src, w.dst, w.maps[0])
+    assert p.info.row_bytes == 10240 and p.info.dst_rows_per_buf == 16384
+    assert p.info.n_tiles >= p.info.boundary_bytes // hp.hp_get_option("tile_bytes")
+    w = wl.large_scale()
+    p = hp.hp_plan_create_host(w.src, w.dst, w.maps[0])
+    assert (p.info.n_src_bufs, p.info.n_dst_bufs, p.info.src_copies, p.info.dst_copies) == (32, 32, 2, 8)
+
+
+def test_empty_map_is_a_valid_empty_plan():
+    tm = wl.TokenMap(2, 16, 8, [], [], [])
+    p = hp.hp_plan_create_host(wl.Grid(dp=2), wl.Grid(tp=2, cp=2), tm)
+    assert p.info.n_rows == 0 and p.info.n_tiles == 0 and p.src_rows() == [0, 0]
+
+
+def _code(src, dst, tm):
+    with pytest.raises(hp.HpError) as e:
+        hp.hp_plan_create_host(src, dst, tm)
+    return e.value.code
+
+
+def test_error_codes():
+    ok = wl.TokenMap(2, 16, 8, [0, 1], [0, 4], [4, 4])
+    g = wl.Grid()
+    assert _code(wl.Grid(tp=0), g, ok) == binding.HP_EINVAL
+    assert _code(g, wl.Grid(cp_split=7), ok) == binding.HP_EINVAL
+    assert _code(g, wl.Grid(row_order=2), ok) == binding.HP_EINVAL
+    assert _code(g, wl.Grid(tp_mode=5), ok) == binding.HP_EINVAL
+    assert _code(g, g, replace(ok, hidden=0)) == binding.HP_EINVAL
+    assert _code(wl.Grid(cp=2), g, ok) == binding.HP_ELAYOUT            # encoder has CP = 1
+    assert _code(g, wl.Grid(dp=3), ok) == binding.HP_ELAYOUT            # batch % DP
+    assert _code(g, wl.Grid(cp=3), ok) == binding.HP_ELAYOUT            # seq % CP
+    assert _code(g, wl.Grid(cp=8, cp_split=wl.CP_ZIGZAG), replace(ok, seq=24)) == binding.HP_ELAYOUT
+    assert _code(g, wl.Grid(tp=3, tp_mode=wl.TP_SEQ_SHARD), ok) == binding.HP_ELAYOUT
+    assert _code(wl.Grid(dp=200), wl.Grid(tp=8, cp=4), ok) == binding.HP_ELAYOUT   # too many buffers
+    assert _code(g, wl.Grid(tp=32), ok) == binding.HP_ELAYOUT
+    bad = lambda **kw: replace(ok, **{k: np.array(v, np.int32) for k, v in kw.items()})
+    assert _code(g, g, bad(img_start=[0, 14])) == binding.HP_EMAP        # runs past the end
+    assert _code(g, g, bad(img_start=[-1, 4])) == binding.HP_EMAP
+    assert _code(g, g, bad(img_len=[0, 4])) == binding.HP_EMAP
+    assert _code(g, g, bad(img_sample=[0, 2])) == binding.HP_EMAP        # sample out of range
+    assert _code(g, g, bad(img_sample=[1, 0])) == binding.HP_EMAP        # not in batch order
+    assert _code(g, g, bad(img_sample=[0, 0], img_start=[0, 3])) == binding.HP_EMAP   # overlap
+    assert _code(wl.Grid(dp=2), g, bad(img_src_dp=[1, 0])) == binding.HP_EMAP
+    assert _code(wl.Grid(dp=2), g, bad(img_src_dp=[0, 2])) == binding.HP_EMAP
+    # touching spans and out-of-order starts inside a sample are legal
+    hp.hp_plan_create_host(g, g, bad(img_sample=[0, 0], img_start=[4, 0]))
+
+
+def test_null_arguments_and_host_only_state():
+    L = binding._lib()
+    out = C.c_void_p(0)
+    assert L.hp_plan_create_host(None, None, None, C.byref(out)) == binding.HP_EINVAL
+    assert not out.value
+    assert L.hp_plan_query(None, None) == binding.HP_EINVAL
+    L.hp_plan_destroy(None)
+    p = hp.hp_plan_create_host(wl.Grid(), wl.Grid(), wl.TokenMap(1, 4, 8, [0], [0], [4]))
+    ptr = (C.c_void_p * 1)(C.c_void_p(64))
+    assert L.hp_forward(p._h, ptr, ptr, None) == binding.HP_ESTATE      # no device tables
+    assert L.hp_backward(p._h, ptr, ptr, None) == binding.HP_ESTATE
+    assert L.hp_forward(p._h, None, ptr, None) == binding.HP_EINVAL
+    assert b"token map" in L.hp_strerror(binding.HP_EMAP)
+    assert L.hp_set_option(b"no_such_key", 1) == binding.HP_EINVAL
+    assert L.hp_set_option(b"block_threads", 100) == binding.HP_EINVAL
+    assert hp.hp_get_option("block_threads") % 64 == 0
