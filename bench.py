@@ -23,6 +23,8 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+OPTION_KEYS = ("tile_bytes", "block_threads_fwd", "block_threads_bwd", "nontemporal_fwd", "nontemporal_bwd",
+               "waves_per_cu_fwd", "waves_per_cu_bwd")
 
 
 def log(*a):
@@ -53,9 +55,8 @@ def main() -> int:
     ap.add_argument("--workload", default="long_context",
                     choices=["tiny", "colocated4", "long_context", "non_colocated", "large_scale"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--tile-bytes", type=int, default=None)
-    ap.add_argument("--block-threads", type=int, default=None)
-    ap.add_argument("--nontemporal", type=int, default=None)
+    ap.add_argument("--option", action="append", default=[], metavar="KEY=INT",
+                    help="library tuning knob, e.g. tile_bytes=4096 (see hp_set_option)")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
@@ -72,10 +73,9 @@ def main() -> int:
         return 3
     torch.cuda.set_device(0)
     dev = "cuda:0"
-    for key, val in (("tile_bytes", args.tile_bytes), ("block_threads", args.block_threads),
-                     ("nontemporal", args.nontemporal)):
-        if val is not None:
-            hp.hp_set_option(key, val)
+    for kv in args.option:
+        key, val = kv.split("=", 1)
+        hp.hp_set_option(key, int(val))
 
     w = wl.CONFIGS[args.workload]()
     maps = w.maps
@@ -219,9 +219,7 @@ def main() -> int:
                    "dst": f"tp{w.dst.tp}cp{w.dst.cp}dp{w.dst.dp}",
                    "batch": maps[0].batch, "seq": maps[0].seq, "hidden": H, "microbatches": len(maps),
                    "image_rows": int(sum(m.n_rows for m in maps)), "boundary_bytes": boundary,
-                   "tile_bytes": hp.hp_get_option("tile_bytes"),
-                   "block_threads": hp.hp_get_option("block_threads"),
-                   "nontemporal": hp.hp_get_option("nontemporal")},
+                   **{k: hp.hp_get_option(k) for k in OPTION_KEYS}},
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
         "forward": {"bytes": fwd_bytes, "median_ms": f_med, "min_ms": min(fwd_ms), "max_ms": max(fwd_ms),
                     "GBps": fwd_bytes / f_med / 1e6, "pct_of_hbm_peak": fwd_bytes / f_med / 1e6 / HBM_PEAK_GBPS * 100},

@@ -214,9 +214,18 @@ int hp_backward(const hp_plan_t *plan, const void *const *dst_grad_bufs,
                 void *const *src_grad_bufs, void *stream);
 
 /* Process-wide tuning knobs (integers).  Known keys:
- *   "tile_bytes"    bytes of boundary data per workgroup (plans created later)
- *   "block_threads" workgroup size, multiple of 64 in [64, 1024]
- *   "nontemporal"   1 = streaming (non-temporal) loads and stores
+ *   "tile_bytes"          bytes of boundary data per workgroup (used by plans
+ *                         created afterwards), 256 .. 16 MiB
+ *   "block_threads_fwd", "block_threads_bwd"
+ *                         workgroup size of the hp_forward / hp_backward kernel,
+ *                         a multiple of 64 in [64, 1024]
+ *   "nontemporal_fwd", "nontemporal_bwd"
+ *                         bit 0 = streaming (non-temporal) loads, bit 1 =
+ *                         streaming stores
+ *   "waves_per_cu_fwd", "waves_per_cu_bwd"
+ *                         cap on resident waves per compute unit (0 = no cap);
+ *                         both kernels reach their best HBM rate below full
+ *                         occupancy
  * Returns HP_EINVAL for an unknown key or an out-of-range value. */
 int hp_set_option(const char *key, int64_t value);
 int64_t hp_get_option(const char *key);     /* INT64_MIN for an unknown key */

@@ -53,7 +53,7 @@ constexpr int kUnroll = 4;
 // ---------------------------------------------------------------------------
 // forward: tile of the source buffer -> the same bytes in NREP destination copies
 // ---------------------------------------------------------------------------
-template <typename V, int NREP, bool NT>
+template <typename V, int NREP, bool NTL, bool NTS>
 __global__ void __launch_bounds__(1024)
 hp_forward_kernel(const hp::Tile *__restrict__ tiles, const BufTable bufs,
                   const uint32_t dst_base, const uint32_t row_bytes, const uint32_t nrep_rt) {
@@ -69,7 +69,7 @@ hp_forward_kernel(const hp::Tile *__restrict__ tiles, const BufTable bufs,
 #pragma unroll
             for (int u = 0; u < kUnroll; ++u) {
                 const uint32_t i = i0 + u * step;
-                if (i < n) v[u] = ld<V, NT>((const V *)src + i);
+                if (i < n) v[u] = ld<V, NTL>((const V *)src + i);
             }
 #pragma unroll 4
             for (uint32_t r = 0; r < nrep; ++r) {
@@ -77,7 +77,7 @@ hp_forward_kernel(const hp::Tile *__restrict__ tiles, const BufTable bufs,
 #pragma unroll
                 for (int u = 0; u < kUnroll; ++u) {
                     const uint32_t i = i0 + u * step;
-                    if (i < n) st<V, NT>((V *)dst + i, v[u]);
+                    if (i < n) st<V, NTS>((V *)dst + i, v[u]);
                 }
             }
         }
@@ -88,10 +88,10 @@ hp_forward_kernel(const hp::Tile *__restrict__ tiles, const BufTable bufs,
             const uint32_t byte = i * (uint32_t)sizeof(V);
             const uint32_t row = byte / row_bytes;
             const uint32_t col = byte - row * row_bytes;
-            const V v = ld<V, NT>((const V *)(src + byte));
+            const V v = ld<V, NTL>((const V *)(src + byte));
             for (uint32_t r = 0; r < nrep; ++r) {
                 char *dst = (char *)bufs.p[dst_base + t.dst_buf0 + r] + t.dst_off;
-                st<V, NT>((V *)(dst + row * pitch + col), v);
+                st<V, NTS>((V *)(dst + row * pitch + col), v);
             }
         }
     }
@@ -116,7 +116,7 @@ template <int W> struct Chunk { typedef uint32_t type __attribute__((ext_vector_
 template <> struct Chunk<1> { typedef uint32_t type; };
 template <> struct Chunk<0> { typedef uint16_t type; };
 
-template <int W, bool NT>
+template <int W>
 struct Fold {
     typedef typename Chunk<W>::type V;
     static constexpr int kElems = W == 0 ? 1 : 2 * W;
@@ -157,7 +157,7 @@ struct Fold {
 
 constexpr int kBwdUnroll = 2;
 
-template <int W, int NREP, bool NT>
+template <int W, int NREP, bool NTL, bool NTS>
 __global__ void __launch_bounds__(1024)
 hp_backward_kernel(const hp::Tile *__restrict__ tiles, const BufTable bufs,
                    const uint32_t dst_base, const uint32_t row_bytes,
@@ -171,7 +171,7 @@ hp_backward_kernel(const hp::Tile *__restrict__ tiles, const BufTable bufs,
     const bool dense = t.pitch_rows == 1;
 
     for (uint32_t i0 = threadIdx.x; i0 < n; i0 += step * kBwdUnroll) {
-        Fold<W, NT> f[kBwdUnroll];
+        Fold<W> f[kBwdUnroll];
         uint64_t goff[kBwdUnroll];
 #pragma unroll
         for (int u = 0; u < kBwdUnroll; ++u) {
@@ -191,7 +191,7 @@ hp_backward_kernel(const hp::Tile *__restrict__ tiles, const BufTable bufs,
             for (int u = 0; u < kBwdUnroll; ++u) {
                 const uint32_t i = i0 + u * step;
                 if (i < n) {
-                    const V v = ld<V, NT>((const V *)(g + goff[u]));
+                    const V v = ld<V, NTL>((const V *)(g + goff[u]));
                     if (r == 0) f[u].first(v); else f[u].add(v);
                 }
             }
@@ -201,7 +201,7 @@ hp_backward_kernel(const hp::Tile *__restrict__ tiles, const BufTable bufs,
 #pragma unroll
             for (int u = 0; u < kBwdUnroll; ++u) {
                 const uint32_t i = i0 + u * step;
-                if (i < n) st<V, NT>((V *)out + i, f[u].result());
+                if (i < n) st<V, NTS>((V *)out + i, f[u].result());
             }
         }
     }
@@ -223,50 +223,75 @@ int pick_width(const hp_plan *p, const BufTable &bt, int n_ptrs) {
     return 0;
 }
 
-template <typename V, bool NT>
-void launch_forward_nrep(const hp_plan *p, const BufTable &bt, hipStream_t st, unsigned block) {
-    const dim3 grid((unsigned)p->tiles.size()), blk(block);
+struct LaunchCfg {
+    unsigned block;      // threads per workgroup
+    unsigned lds_bytes;  // dynamic LDS requested only to cap the workgroups resident per CU
+};
+
+// Both kernels run fastest well below full occupancy: with every wave slot
+// busy the in-flight window of addresses is wide and HBM efficiency drops.  The
+// cap is expressed in waves per CU and enforced by requesting a slice of the
+// CU's 160 KB LDS per workgroup (the kernels do not touch it).
+LaunchCfg launch_cfg(int64_t block, int64_t waves_per_cu) {
+    LaunchCfg c{(unsigned)block, 0u};
+    const int64_t waves_per_wg = block / 64;
+    if (waves_per_cu > 0) {
+        int64_t wgs = waves_per_cu / waves_per_wg;
+        if (wgs < 2) wgs = 2;
+        if (wgs < 32) {
+            int64_t lds = (160 * 1024) / wgs - 512;
+            lds = lds / 512 * 512;
+            if (lds > 64 * 1024) lds = 64 * 1024;
+            c.lds_bytes = (unsigned)lds;
+        }
+    }
+    return c;
+}
+
+template <typename V, bool NTL, bool NTS>
+void launch_forward_nrep(const hp_plan *p, const BufTable &bt, hipStream_t st, LaunchCfg c) {
+    const dim3 grid((unsigned)p->tiles.size()), blk(c.block);
     const uint32_t base = (uint32_t)p->n_src_bufs, rb = (uint32_t)p->row_bytes, nrep = (uint32_t)p->dst_copies;
     switch (p->dst_copies) {
-        case 1: hipLaunchKernelGGL((hp_forward_kernel<V, 1, NT>), grid, blk, 0, st, p->d_tiles, bt, base, rb, nrep); break;
-        case 2: hipLaunchKernelGGL((hp_forward_kernel<V, 2, NT>), grid, blk, 0, st, p->d_tiles, bt, base, rb, nrep); break;
-        case 4: hipLaunchKernelGGL((hp_forward_kernel<V, 4, NT>), grid, blk, 0, st, p->d_tiles, bt, base, rb, nrep); break;
-        case 8: hipLaunchKernelGGL((hp_forward_kernel<V, 8, NT>), grid, blk, 0, st, p->d_tiles, bt, base, rb, nrep); break;
-        default: hipLaunchKernelGGL((hp_forward_kernel<V, 0, NT>), grid, blk, 0, st, p->d_tiles, bt, base, rb, nrep); break;
+        case 1: hipLaunchKernelGGL((hp_forward_kernel<V, 1, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep); break;
+        case 2: hipLaunchKernelGGL((hp_forward_kernel<V, 2, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep); break;
+        case 4: hipLaunchKernelGGL((hp_forward_kernel<V, 4, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep); break;
+        case 8: hipLaunchKernelGGL((hp_forward_kernel<V, 8, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep); break;
+        default: hipLaunchKernelGGL((hp_forward_kernel<V, 0, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep); break;
     }
 }
 
-template <bool NT>
-void launch_forward(const hp_plan *p, const BufTable &bt, hipStream_t st, unsigned block, int width) {
+template <bool NTL, bool NTS>
+void launch_forward(const hp_plan *p, const BufTable &bt, hipStream_t st, LaunchCfg c, int width) {
     switch (width) {
-        case 16: launch_forward_nrep<u32x4, NT>(p, bt, st, block); break;
-        case 8: launch_forward_nrep<u32x2, NT>(p, bt, st, block); break;
-        case 4: launch_forward_nrep<uint32_t, NT>(p, bt, st, block); break;
-        default: launch_forward_nrep<uint16_t, NT>(p, bt, st, block); break;
+        case 16: launch_forward_nrep<u32x4, NTL, NTS>(p, bt, st, c); break;
+        case 8: launch_forward_nrep<u32x2, NTL, NTS>(p, bt, st, c); break;
+        case 4: launch_forward_nrep<uint32_t, NTL, NTS>(p, bt, st, c); break;
+        default: launch_forward_nrep<uint16_t, NTL, NTS>(p, bt, st, c); break;
     }
 }
 
-template <int W, bool NT>
-void launch_backward_nrep(const hp_plan *p, const BufTable &bt, hipStream_t st, unsigned block) {
-    const dim3 grid((unsigned)p->tiles.size()), blk(block);
+template <int W, bool NTL, bool NTS>
+void launch_backward_nrep(const hp_plan *p, const BufTable &bt, hipStream_t st, LaunchCfg c) {
+    const dim3 grid((unsigned)p->tiles.size()), blk(c.block);
     const uint32_t base = (uint32_t)p->n_src_bufs, rb = (uint32_t)p->row_bytes;
     const uint32_t nrep = (uint32_t)p->dst_copies, sc = (uint32_t)p->src_copies;
     switch (p->dst_copies) {
-        case 1: hipLaunchKernelGGL((hp_backward_kernel<W, 1, NT>), grid, blk, 0, st, p->d_tiles, bt, base, rb, nrep, sc); break;
-        case 2: hipLaunchKernelGGL((hp_backward_kernel<W, 2, NT>), grid, blk, 0, st, p->d_tiles, bt, base, rb, nrep, sc); break;
-        case 4: hipLaunchKernelGGL((hp_backward_kernel<W, 4, NT>), grid, blk, 0, st, p->d_tiles, bt, base, rb, nrep, sc); break;
-        case 8: hipLaunchKernelGGL((hp_backward_kernel<W, 8, NT>), grid, blk, 0, st, p->d_tiles, bt, base, rb, nrep, sc); break;
-        default: hipLaunchKernelGGL((hp_backward_kernel<W, 0, NT>), grid, blk, 0, st, p->d_tiles, bt, base, rb, nrep, sc); break;
+        case 1: hipLaunchKernelGGL((hp_backward_kernel<W, 1, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep, sc); break;
+        case 2: hipLaunchKernelGGL((hp_backward_kernel<W, 2, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep, sc); break;
+        case 4: hipLaunchKernelGGL((hp_backward_kernel<W, 4, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep, sc); break;
+        case 8: hipLaunchKernelGGL((hp_backward_kernel<W, 8, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep, sc); break;
+        default: hipLaunchKernelGGL((hp_backward_kernel<W, 0, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep, sc); break;
     }
 }
 
-template <bool NT>
-void launch_backward(const hp_plan *p, const BufTable &bt, hipStream_t st, unsigned block, int width) {
+template <bool NTL, bool NTS>
+void launch_backward(const hp_plan *p, const BufTable &bt, hipStream_t st, LaunchCfg c, int width) {
     switch (width) {
-        case 16: launch_backward_nrep<4, NT>(p, bt, st, block); break;
-        case 8: launch_backward_nrep<2, NT>(p, bt, st, block); break;
-        case 4: launch_backward_nrep<1, NT>(p, bt, st, block); break;
-        default: launch_backward_nrep<0, NT>(p, bt, st, block); break;
+        case 16: launch_backward_nrep<4, NTL, NTS>(p, bt, st, c); break;
+        case 8: launch_backward_nrep<2, NTL, NTS>(p, bt, st, c); break;
+        case 4: launch_backward_nrep<1, NTL, NTS>(p, bt, st, c); break;
+        default: launch_backward_nrep<0, NTL, NTS>(p, bt, st, c); break;
     }
 }
 
@@ -337,6 +362,21 @@ int create_common(const hp_layout_t *src, const hp_layout_t *dst, const hp_token
     return HP_OK;
 }
 
+struct OptionDesc {
+    const char *name;
+    int64_t hp::Options::*field;
+    int64_t lo, hi, multiple;
+};
+const OptionDesc kOptions[] = {
+    {"tile_bytes", &hp::Options::tile_bytes, 256, 1 << 24, 1},
+    {"block_threads_fwd", &hp::Options::block_threads_fwd, 64, 1024, 64},
+    {"block_threads_bwd", &hp::Options::block_threads_bwd, 64, 1024, 64},
+    {"nontemporal_fwd", &hp::Options::nontemporal_fwd, 0, 3, 1},
+    {"nontemporal_bwd", &hp::Options::nontemporal_bwd, 0, 3, 1},
+    {"waves_per_cu_fwd", &hp::Options::waves_per_cu_fwd, 0, 32, 1},
+    {"waves_per_cu_bwd", &hp::Options::waves_per_cu_bwd, 0, 32, 1},
+};
+
 }  // namespace
 
 extern "C" {
@@ -398,9 +438,13 @@ int hp_forward(const hp_plan_t *p, const void *const *src_bufs, void *const *dst
     int rc = prepare(p, src_bufs, (const void *const *)dst_bufs, false, &bt, &width);
     if (rc != HP_OK) return rc;
     if (p->tiles.empty()) return HP_OK;
-    const unsigned block = (unsigned)hp::options().block_threads;
-    if (hp::options().nontemporal) launch_forward<true>(p, bt, (hipStream_t)stream, block, width);
-    else launch_forward<false>(p, bt, (hipStream_t)stream, block, width);
+    const LaunchCfg block = launch_cfg(hp::options().block_threads_fwd, hp::options().waves_per_cu_fwd);
+    switch (hp::options().nontemporal_fwd & 3) {
+        case 0: launch_forward<false, false>(p, bt, (hipStream_t)stream, block, width); break;
+        case 1: launch_forward<true, false>(p, bt, (hipStream_t)stream, block, width); break;
+        case 2: launch_forward<false, true>(p, bt, (hipStream_t)stream, block, width); break;
+        default: launch_forward<true, true>(p, bt, (hipStream_t)stream, block, width); break;
+    }
     return finish_launch();
 }
 
@@ -411,35 +455,31 @@ int hp_backward(const hp_plan_t *p, const void *const *dst_grad_bufs, void *cons
     int rc = prepare(p, (const void *const *)src_grad_bufs, dst_grad_bufs, true, &bt, &width);
     if (rc != HP_OK) return rc;
     if (p->tiles.empty()) return HP_OK;
-    const unsigned block = (unsigned)hp::options().block_threads;
-    if (hp::options().nontemporal) launch_backward<true>(p, bt, (hipStream_t)stream, block, width);
-    else launch_backward<false>(p, bt, (hipStream_t)stream, block, width);
+    const LaunchCfg block = launch_cfg(hp::options().block_threads_bwd, hp::options().waves_per_cu_bwd);
+    switch (hp::options().nontemporal_bwd & 3) {
+        case 0: launch_backward<false, false>(p, bt, (hipStream_t)stream, block, width); break;
+        case 1: launch_backward<true, false>(p, bt, (hipStream_t)stream, block, width); break;
+        case 2: launch_backward<false, true>(p, bt, (hipStream_t)stream, block, width); break;
+        default: launch_backward<true, true>(p, bt, (hipStream_t)stream, block, width); break;
+    }
     return finish_launch();
 }
 
 int hp_set_option(const char *key, int64_t value) {
     if (!key) return HP_EINVAL;
-    hp::Options &o = hp::options();
-    if (!std::strcmp(key, "tile_bytes")) {
-        if (value < 256 || value > (1 << 24)) return HP_EINVAL;
-        o.tile_bytes = value;
-    } else if (!std::strcmp(key, "block_threads")) {
-        if (value < 64 || value > 1024 || value % 64) return HP_EINVAL;
-        o.block_threads = value;
-    } else if (!std::strcmp(key, "nontemporal")) {
-        if (value != 0 && value != 1) return HP_EINVAL;
-        o.nontemporal = value;
-    } else {
-        return HP_EINVAL;
+    for (const OptionDesc &d : kOptions) {
+        if (std::strcmp(key, d.name)) continue;
+        if (value < d.lo || value > d.hi || (d.multiple > 1 && value % d.multiple)) return HP_EINVAL;
+        hp::options().*(d.field) = value;
+        return HP_OK;
     }
-    return HP_OK;
+    return HP_EINVAL;
 }
 
 int64_t hp_get_option(const char *key) {
-    const hp::Options &o = hp::options();
-    if (key && !std::strcmp(key, "tile_bytes")) return o.tile_bytes;
-    if (key && !std::strcmp(key, "block_threads")) return o.block_threads;
-    if (key && !std::strcmp(key, "nontemporal")) return o.nontemporal;
+    if (key)
+        for (const OptionDesc &d : kOptions)
+            if (!std::strcmp(key, d.name)) return hp::options().*(d.field);
     return INT64_MIN;
 }
 

@@ -22,9 +22,13 @@ struct alignas(16) Tile {
 static_assert(sizeof(Tile) == 32, "tile table entry must stay 32 bytes");
 
 struct Options {
-    int64_t tile_bytes = 32768;
-    int64_t block_threads = 256;
-    int64_t nontemporal = 1;
+    int64_t tile_bytes = 8192;
+    int64_t block_threads_fwd = 256;
+    int64_t block_threads_bwd = 256;
+    int64_t waves_per_cu_fwd = 8;   // 0 = no cap
+    int64_t waves_per_cu_bwd = 12;
+    int64_t nontemporal_fwd = 2;  // bit 0: streaming loads, bit 1: streaming stores
+    int64_t nontemporal_bwd = 3;
 };
 Options &options();
 

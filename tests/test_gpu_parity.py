@@ -18,7 +18,8 @@ pytestmark = pytest.mark.gpu
 
 @pytest.fixture(autouse=True)
 def _default_options():
-    saved = {k: hp.hp_get_option(k) for k in ("tile_bytes", "block_threads", "nontemporal")}
+    saved = {k: hp.hp_get_option(k) for k in ("tile_bytes", "block_threads_fwd", "block_threads_bwd", "nontemporal_fwd", "nontemporal_bwd",
+                                             "waves_per_cu_fwd", "waves_per_cu_bwd")}
     yield
     for k, v in saved.items():
         hp.hp_set_option(k, v)
@@ -52,12 +53,17 @@ def test_long_context_spans_at_several_hidden_sizes(hidden):
     check_case(w.src, w.dst, tm, seed=hidden)
 
 
-@pytest.mark.parametrize("tile,block,nt", [(256, 64, 1), (1024, 128, 0), (32768, 256, 1),
-                                          (65536, 512, 0), (1 << 20, 1024, 1)])
-def test_launch_shapes(tile, block, nt):
+@pytest.mark.parametrize("tile,block,nt,waves", [(256, 64, 1, 0), (1024, 128, 0, 4), (32768, 256, 2, 8),
+                                                (65536, 512, 3, 16), (1 << 20, 1024, 1, 32),
+                                                (4096, 256, 2, 12), (2048, 64, 3, 1)])
+def test_launch_shapes(tile, block, nt, waves):
     hp.hp_set_option("tile_bytes", tile)
-    hp.hp_set_option("block_threads", block)
-    hp.hp_set_option("nontemporal", nt)
+    hp.hp_set_option("block_threads_fwd", block)
+    hp.hp_set_option("block_threads_bwd", 1024 // (block // 64))
+    hp.hp_set_option("waves_per_cu_fwd", waves)
+    hp.hp_set_option("waves_per_cu_bwd", 32 - waves)
+    hp.hp_set_option("nontemporal_fwd", nt)
+    hp.hp_set_option("nontemporal_bwd", 3 - nt)
     w = wl.scaled(wl.large_scale(), 96)
     check_case(w.src, w.dst, w.maps[0], seed=tile % 97)
 

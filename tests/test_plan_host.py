@@ -150,5 +150,7 @@ def test_null_arguments_and_host_only_state():
     assert L.hp_forward(p._h, None, ptr, None) == binding.HP_EINVAL
     assert b"token map" in L.hp_strerror(binding.HP_EMAP)
     assert L.hp_set_option(b"no_such_key", 1) == binding.HP_EINVAL
-    assert L.hp_set_option(b"block_threads", 100) == binding.HP_EINVAL
-    assert hp.hp_get_option("block_threads") % 64 == 0
+    assert L.hp_set_option(b"block_threads_fwd", 100) == binding.HP_EINVAL
+    assert L.hp_set_option(b"waves_per_cu_bwd", 33) == binding.HP_EINVAL
+    assert hp.hp_get_option("block_threads_fwd") % 64 == 0
+    assert hp.hp_get_option("nope") == -2 ** 63
