@@ -230,6 +230,17 @@ int hp_backward(const hp_plan_t *plan, const void *const *dst_grad_bufs,
 int hp_set_option(const char *key, int64_t value);
 int64_t hp_get_option(const char *key);     /* INT64_MIN for an unknown key */
 
+/* Kernel timing for measurement harnesses.  hp_profile_enable(n) with n > 0
+ * creates n HIP event pairs; from then on each hp_forward / hp_backward launch
+ * (in call order, any thread) is stamped with the begin and end time of its own
+ * kernel dispatch until the n pairs are used up; later launches are not timed.
+ * n = 0 disables timing and frees the events.  hp_profile_read waits for the
+ * recorded launches, writes their kernel durations in milliseconds to ms[] and
+ * their kind (0 = hp_forward, 1 = hp_backward) to kinds[] (host arrays of `cap`
+ * entries), rewinds the recorder and returns the number of launches recorded. */
+int hp_profile_enable(int32_t max_launches);
+int hp_profile_read(float *ms, int32_t *kinds, int32_t cap);
+
 const char *hp_strerror(int code);
 /* hipError_t value of the most recent failing HIP call on this thread (0 if none). */
 int hp_last_hip_error(void);

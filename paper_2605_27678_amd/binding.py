@@ -60,7 +60,7 @@ class hp_segment_t(C.Structure):
 
 EXPORTS = ["hp_plan_create", "hp_plan_create_host", "hp_plan_destroy", "hp_plan_query",
            "hp_plan_src_rows", "hp_plan_segments", "hp_forward", "hp_backward",
-           "hp_set_option", "hp_get_option", "hp_strerror", "hp_last_hip_error", "hp_version"]
+           "hp_set_option", "hp_get_option", "hp_profile_enable", "hp_profile_read", "hp_strerror", "hp_last_hip_error", "hp_version"]
 
 _handle = None
 
@@ -89,11 +89,14 @@ def _lib():
     L.hp_set_option.argtypes = [C.c_char_p, i64]
     L.hp_get_option.argtypes = [C.c_char_p]
     L.hp_get_option.restype = i64
+    L.hp_profile_enable.argtypes = [i32]
+    L.hp_profile_read.argtypes = [C.POINTER(C.c_float), C.POINTER(i32), i32]
     L.hp_strerror.argtypes = [C.c_int]
     L.hp_strerror.restype = C.c_char_p
     L.hp_version.restype = C.c_char_p
     for f in ("hp_plan_create", "hp_plan_create_host", "hp_plan_query", "hp_plan_src_rows",
-              "hp_plan_segments", "hp_forward", "hp_backward", "hp_set_option", "hp_last_hip_error"):
+              "hp_plan_segments", "hp_forward", "hp_backward", "hp_set_option", "hp_last_hip_error",
+              "hp_profile_enable", "hp_profile_read"):
         getattr(L, f).restype = C.c_int
     _handle = L
     return L
@@ -127,6 +130,19 @@ def hp_set_option(key: str, value: int) -> None:
 
 def hp_get_option(key: str) -> int:
     return int(_lib().hp_get_option(key.encode()))
+
+
+def hp_profile_enable(max_launches: int) -> None:
+    _check(_lib().hp_profile_enable(int(max_launches)), "hp_profile_enable")
+
+
+def hp_profile_read(cap: int):
+    """[(kind, milliseconds)] of the launches recorded since the last read;
+    kind 0 = hp_forward, 1 = hp_backward."""
+    ms = (C.c_float * max(cap, 1))()
+    kinds = (C.c_int32 * max(cap, 1))()
+    n = _check(_lib().hp_profile_read(ms, kinds, cap), "hp_profile_read")
+    return [(int(kinds[i]), float(ms[i])) for i in range(min(n, cap))]
 
 
 def hp_version() -> str:

@@ -9,10 +9,13 @@
 // needed because a lane owns the same eight elements of every replica), rounds
 // once to bf16 and stores to all source TP copies.
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 
 #include <cstdint>
 #include <cstring>
+#include <mutex>
 #include <new>
+#include <vector>
 
 #include "hp.h"
 #include "hp_plan.hpp"
@@ -223,6 +226,39 @@ int pick_width(const hp_plan *p, const BufTable &bt, int n_ptrs) {
     return 0;
 }
 
+// Optional per-launch kernel timing.  When enabled, every launch is given its own
+// pair of HIP events through hipExtLaunchKernelGGL, which stamps them with the
+// dispatch's own begin and end times (no extra marker packets in the stream, so
+// the timed work is not perturbed).
+struct Profiler {
+    std::mutex mu;
+    std::vector<hipEvent_t> start, stop;
+    std::vector<int32_t> kind;
+    size_t used = 0;
+    bool enabled = false;
+} g_prof;
+
+struct EventPair { hipEvent_t start = nullptr, stop = nullptr; };
+
+EventPair next_event_pair(int kind) {
+    EventPair e;
+    if (!g_prof.enabled) return e;
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    if (g_prof.enabled && g_prof.used < g_prof.start.size()) {
+        e.start = g_prof.start[g_prof.used];
+        e.stop = g_prof.stop[g_prof.used];
+        g_prof.kind[g_prof.used] = kind;
+        ++g_prof.used;
+    }
+    return e;
+}
+
+#define HP_LAUNCH(kind, kernel, grid, blk, lds, st, ...)                                        \
+    do {                                                                                        \
+        const EventPair ev_ = next_event_pair(kind);                                            \
+        hipExtLaunchKernelGGL(kernel, grid, blk, lds, st, ev_.start, ev_.stop, 0, __VA_ARGS__); \
+    } while (0)
+
 struct LaunchCfg {
     unsigned block;      // threads per workgroup
     unsigned lds_bytes;  // dynamic LDS requested only to cap the workgroups resident per CU
@@ -253,11 +289,11 @@ void launch_forward_nrep(const hp_plan *p, const BufTable &bt, hipStream_t st, L
     const dim3 grid((unsigned)p->tiles.size()), blk(c.block);
     const uint32_t base = (uint32_t)p->n_src_bufs, rb = (uint32_t)p->row_bytes, nrep = (uint32_t)p->dst_copies;
     switch (p->dst_copies) {
-        case 1: hipLaunchKernelGGL((hp_forward_kernel<V, 1, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep); break;
-        case 2: hipLaunchKernelGGL((hp_forward_kernel<V, 2, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep); break;
-        case 4: hipLaunchKernelGGL((hp_forward_kernel<V, 4, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep); break;
-        case 8: hipLaunchKernelGGL((hp_forward_kernel<V, 8, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep); break;
-        default: hipLaunchKernelGGL((hp_forward_kernel<V, 0, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep); break;
+        case 1: HP_LAUNCH(0, (hp_forward_kernel<V, 1, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep); break;
+        case 2: HP_LAUNCH(0, (hp_forward_kernel<V, 2, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep); break;
+        case 4: HP_LAUNCH(0, (hp_forward_kernel<V, 4, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep); break;
+        case 8: HP_LAUNCH(0, (hp_forward_kernel<V, 8, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep); break;
+        default: HP_LAUNCH(0, (hp_forward_kernel<V, 0, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep); break;
     }
 }
 
@@ -277,11 +313,11 @@ void launch_backward_nrep(const hp_plan *p, const BufTable &bt, hipStream_t st, 
     const uint32_t base = (uint32_t)p->n_src_bufs, rb = (uint32_t)p->row_bytes;
     const uint32_t nrep = (uint32_t)p->dst_copies, sc = (uint32_t)p->src_copies;
     switch (p->dst_copies) {
-        case 1: hipLaunchKernelGGL((hp_backward_kernel<W, 1, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep, sc); break;
-        case 2: hipLaunchKernelGGL((hp_backward_kernel<W, 2, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep, sc); break;
-        case 4: hipLaunchKernelGGL((hp_backward_kernel<W, 4, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep, sc); break;
-        case 8: hipLaunchKernelGGL((hp_backward_kernel<W, 8, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep, sc); break;
-        default: hipLaunchKernelGGL((hp_backward_kernel<W, 0, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep, sc); break;
+        case 1: HP_LAUNCH(1, (hp_backward_kernel<W, 1, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep, sc); break;
+        case 2: HP_LAUNCH(1, (hp_backward_kernel<W, 2, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep, sc); break;
+        case 4: HP_LAUNCH(1, (hp_backward_kernel<W, 4, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep, sc); break;
+        case 8: HP_LAUNCH(1, (hp_backward_kernel<W, 8, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep, sc); break;
+        default: HP_LAUNCH(1, (hp_backward_kernel<W, 0, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep, sc); break;
     }
 }
 
@@ -481,6 +517,51 @@ int64_t hp_get_option(const char *key) {
         for (const OptionDesc &d : kOptions)
             if (!std::strcmp(key, d.name)) return hp::options().*(d.field);
     return INT64_MIN;
+}
+
+int hp_profile_enable(int32_t max_launches) {
+    if (max_launches < 0 || max_launches > (1 << 20)) return HP_EINVAL;
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    g_prof.enabled = false;
+    for (hipEvent_t e : g_prof.start) (void)hipEventDestroy(e);
+    for (hipEvent_t e : g_prof.stop) (void)hipEventDestroy(e);
+    g_prof.start.clear(); g_prof.stop.clear(); g_prof.kind.clear();
+    g_prof.used = 0;
+    if (max_launches == 0) return HP_OK;
+    try {
+        g_prof.start.reserve(max_launches); g_prof.stop.reserve(max_launches);
+        g_prof.kind.assign(max_launches, 0);
+    } catch (const std::bad_alloc &) {
+        return HP_ENOMEM;
+    }
+    for (int32_t i = 0; i < max_launches; ++i) {
+        hipEvent_t a = nullptr, b = nullptr;
+        if (hip_failed(hipEventCreate(&a)) || hip_failed(hipEventCreate(&b))) {
+            if (a) (void)hipEventDestroy(a);
+            for (hipEvent_t e : g_prof.start) (void)hipEventDestroy(e);
+            for (hipEvent_t e : g_prof.stop) (void)hipEventDestroy(e);
+            g_prof.start.clear(); g_prof.stop.clear(); g_prof.kind.clear();
+            return HP_EHIP;
+        }
+        g_prof.start.push_back(a); g_prof.stop.push_back(b);
+    }
+    g_prof.enabled = true;
+    return HP_OK;
+}
+
+int hp_profile_read(float *ms, int32_t *kinds, int32_t cap) {
+    if (cap < 0 || (cap > 0 && (!ms || !kinds))) return HP_EINVAL;
+    std::lock_guard<std::mutex> lk(g_prof.mu);
+    const int32_t n = (int32_t)g_prof.used;
+    for (int32_t i = 0; i < n && i < cap; ++i) {
+        if (hip_failed(hipEventSynchronize(g_prof.stop[i]))) return HP_EHIP;
+        float t = 0.f;
+        if (hip_failed(hipEventElapsedTime(&t, g_prof.start[i], g_prof.stop[i]))) return HP_EHIP;
+        ms[i] = t;
+        kinds[i] = g_prof.kind[i];
+    }
+    g_prof.used = 0;
+    return n;
 }
 
 const char *hp_strerror(int code) {

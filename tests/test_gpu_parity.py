@@ -203,6 +203,29 @@ def test_caller_stream_and_determinism():
     assert all(torch.equal(a, b) for a, b in zip(*outs))
 
 
+def test_profile_records_kernel_durations():
+    w = wl.scaled(wl.long_context(), 512)
+    plan = hp.hp_plan_create(w.src, w.dst, w.maps[0])
+    src = [wl.random_bf16((r, 512), 1 + i, "cuda") for i, r in enumerate(plan.src_rows())]
+    dst = [torch.zeros((plan.info.dst_rows_per_buf, 512), dtype=torch.bfloat16, device="cuda") for _ in range(32)]
+    sg = [torch.zeros_like(t) for t in src]
+    hp.hp_profile_enable(3)
+    try:
+        hp.hp_forward(plan, src, dst)
+        hp.hp_backward(plan, dst, sg)
+        hp.hp_forward(plan, src, dst)
+        hp.hp_backward(plan, dst, sg)            # beyond the 3 pairs: runs untimed
+        got = hp.hp_profile_read(8)
+        assert [k for k, _ in got] == [0, 1, 0]
+        assert all(0.0 < ms < 50.0 for _, ms in got)
+        assert hp.hp_profile_read(8) == []
+    finally:
+        hp.hp_profile_enable(0)
+    torch.cuda.synchronize()
+    for a, b in zip(sg, src):
+        assert torch.equal(a.float(), 4.0 * b.float())    # four identical replicas summed: exact in bf16
+
+
 # ---- full sizes, in the launch configuration the benchmark times --------------
 
 def test_full_colocated4():

@@ -154,3 +154,7 @@ def test_null_arguments_and_host_only_state():
     assert L.hp_set_option(b"waves_per_cu_bwd", 33) == binding.HP_EINVAL
     assert hp.hp_get_option("block_threads_fwd") % 64 == 0
     assert hp.hp_get_option("nope") == -2 ** 63
+    assert L.hp_profile_enable(-1) == binding.HP_EINVAL
+    assert L.hp_profile_enable(0) == binding.HP_OK
+    assert L.hp_profile_read(None, None, 4) == binding.HP_EINVAL
+    assert L.hp_profile_read(None, None, 0) == 0
