@@ -23,7 +23,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
-OPTION_KEYS = ("tile_bytes", "block_threads_fwd", "block_threads_bwd", "nontemporal_fwd", "nontemporal_bwd",
+OPTION_KEYS = ("tile_bytes_fwd", "tile_bytes_bwd", "block_threads_fwd", "block_threads_bwd", "nontemporal_fwd", "nontemporal_bwd",
                "waves_per_cu_fwd", "waves_per_cu_bwd")
 
 
@@ -56,7 +56,7 @@ def main() -> int:
                     choices=["tiny", "colocated4", "long_context", "non_colocated", "large_scale"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--option", action="append", default=[], metavar="KEY=INT",
-                    help="library tuning knob, e.g. tile_bytes=4096 (see hp_set_option)")
+                    help="library tuning knob, e.g. tile_bytes_fwd=4096 (see hp_set_option)")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:

@@ -87,7 +87,7 @@ extern "C" {
 /* hp_token_map_t.dtype */
 #define HP_BF16 0
 
-#define HP_MAX_BUFFERS 224   /* source + destination buffers of one plan                     */
+#define HP_MAX_BUFFERS 448   /* source + destination buffers of one plan, all microbatches   */
 #define HP_MAX_TP      16    /* replicas summed by hp_backward                               */
 
 /* One module's logical grid G_m and the first id of its physical rank range R_m
@@ -134,9 +134,10 @@ typedef struct hp_plan_info {
     int64_t fwd_bytes;         /* algorithmic traffic of hp_forward: (1 + dst_copies)*boundary */
     int64_t bwd_bytes;         /* of hp_backward: (dst_copies + src_copies)*boundary          */
     int32_t n_segments;        /* runs contiguous on both sides                               */
-    int32_t n_tiles;           /* work items = workgroups per launch                          */
+    int32_t n_tiles;           /* workgroups of an hp_forward launch in its current shape     */
     int32_t on_device;         /* 1 if device tables exist                                    */
     int32_t device;            /* HIP device ordinal of the tables, -1 if none                */
+    int32_t n_maps;            /* microbatches folded into the plan (1 unless batched)        */
 } hp_plan_info_t;
 
 /* A maximal run of image-token rows that is contiguous in the source buffer and
@@ -165,6 +166,19 @@ int hp_plan_create(const hp_layout_t *src, const hp_layout_t *dst,
  * hp_forward / hp_backward on it return HP_ESTATE. */
 int hp_plan_create_host(const hp_layout_t *src, const hp_layout_t *dst,
                         const hp_token_map_t *map, hp_plan_t **out);
+
+/* One plan for n_maps microbatches that share the two grids and the buffer
+ * shapes (same batch, seq, hidden) but have their own token maps and their own
+ * buffers - the packed boundary tensor with per-microbatch views of the
+ * colocated schedule (appendix "Pipeline schedule details", phases 1-3), and
+ * the per-microbatch invocations of the non-colocated communicator folded into
+ * one launch per direction.  Buffer arrays are microbatch-major: source buffer
+ * index m*(TP_src*DP_src) + tp + TP_src*dp, destination buffer index
+ * m*(TP_dst*CP_dst*DP_dst) + tp + TP_dst*(cp + CP_dst*dp); the totals must not
+ * exceed HP_MAX_BUFFERS.  host_only != 0 skips the device upload. */
+int hp_plan_create_batched(const hp_layout_t *src, const hp_layout_t *dst,
+                           const hp_token_map_t *maps, int32_t n_maps,
+                           int32_t host_only, hp_plan_t **out);
 
 /* Frees host and device tables.  NULL is allowed.  The caller must have
  * synchronised every stream that still uses the plan. */
@@ -213,19 +227,34 @@ int hp_forward(const hp_plan_t *plan, const void *const *src_bufs,
 int hp_backward(const hp_plan_t *plan, const void *const *dst_grad_bufs,
                 void *const *src_grad_bufs, void *stream);
 
-/* Process-wide tuning knobs (integers).  Known keys:
- *   "tile_bytes"          bytes of boundary data per workgroup (used by plans
- *                         created afterwards), 256 .. 16 MiB
- *   "block_threads_fwd", "block_threads_bwd"
- *                         workgroup size of the hp_forward / hp_backward kernel,
- *                         a multiple of 64 in [64, 1024]
- *   "nontemporal_fwd", "nontemporal_bwd"
- *                         bit 0 = streaming (non-temporal) loads, bit 1 =
- *                         streaming stores
- *   "waves_per_cu_fwd", "waves_per_cu_bwd"
- *                         cap on resident waves per compute unit (0 = no cap);
- *                         both kernels reach their best HBM rate below full
- *                         occupancy
+/* Launch shape of one direction of a plan (direction 0 = hp_forward,
+ * 1 = hp_backward).  A plan starts from the process-wide defaults below. */
+typedef struct hp_launch {
+    int32_t tile_bytes;      /* boundary bytes per workgroup: 1024 << k, k = 0..6              */
+    int32_t block_threads;   /* workgroup size: multiple of 64 in [64, 1024]                   */
+    int32_t waves_per_cu;    /* cap on resident waves per compute unit, 0 = none; both kernels
+                                reach their best HBM rate well below full occupancy            */
+    int32_t nontemporal;     /* bit 0 = streaming (non-temporal) loads, bit 1 = streaming stores */
+} hp_launch_t;
+int hp_plan_get_launch(const hp_plan_t *plan, int32_t direction, hp_launch_t *out);
+int hp_plan_set_launch(hp_plan_t *plan, int32_t direction, const hp_launch_t *in);
+
+/* Measures a set of launch shapes on the caller's real buffers and keeps the
+ * fastest in the plan (tile size x workgroup size x resident-wave cap; the
+ * best cap depends on the replica count and row size, and the optimum is
+ * narrow).  Arguments as for hp_forward and hp_backward; pass both pointers of
+ * a direction as NULL to leave that direction alone.  The candidate launches
+ * compute exactly what hp_forward / hp_backward compute, so the buffers end up
+ * as after one such call.  SYNCHRONOUS: waits on `stream` repeatedly, takes
+ * tens of milliseconds, creates and destroys two HIP events, and must not run
+ * concurrently with other calls that use the same plan. */
+int hp_plan_tune(hp_plan_t *plan, const void *const *src_bufs, void *const *dst_bufs,
+                 const void *const *dst_grad_bufs, void *const *src_grad_bufs, void *stream);
+
+/* Process-wide defaults copied into every plan created afterwards (integers).
+ * Keys: "tile_bytes_fwd", "tile_bytes_bwd", "block_threads_fwd",
+ * "block_threads_bwd", "waves_per_cu_fwd", "waves_per_cu_bwd",
+ * "nontemporal_fwd", "nontemporal_bwd"; meanings and ranges as in hp_launch_t.
  * Returns HP_EINVAL for an unknown key or an out-of-range value. */
 int hp_set_option(const char *key, int64_t value);
 int64_t hp_get_option(const char *key);     /* INT64_MIN for an unknown key */

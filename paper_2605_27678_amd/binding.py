@@ -50,7 +50,7 @@ class hp_plan_info_t(C.Structure):
                 ("n_rows", C.c_int64), ("row_bytes", C.c_int64), ("dst_rows_per_buf", C.c_int64),
                 ("boundary_bytes", C.c_int64), ("fwd_bytes", C.c_int64), ("bwd_bytes", C.c_int64),
                 ("n_segments", C.c_int32), ("n_tiles", C.c_int32),
-                ("on_device", C.c_int32), ("device", C.c_int32)]
+                ("on_device", C.c_int32), ("device", C.c_int32), ("n_maps", C.c_int32)]
 
 
 class hp_segment_t(C.Structure):
@@ -58,9 +58,16 @@ class hp_segment_t(C.Structure):
                 ("dst_row0", C.c_int64), ("n_rows", C.c_int64), ("dst_row_stride", C.c_int64)]
 
 
-EXPORTS = ["hp_plan_create", "hp_plan_create_host", "hp_plan_destroy", "hp_plan_query",
-           "hp_plan_src_rows", "hp_plan_segments", "hp_forward", "hp_backward",
-           "hp_set_option", "hp_get_option", "hp_profile_enable", "hp_profile_read", "hp_strerror", "hp_last_hip_error", "hp_version"]
+class hp_launch_t(C.Structure):
+    _fields_ = [("tile_bytes", C.c_int32), ("block_threads", C.c_int32),
+                ("waves_per_cu", C.c_int32), ("nontemporal", C.c_int32)]
+
+
+EXPORTS = ["hp_plan_create", "hp_plan_create_host", "hp_plan_create_batched", "hp_plan_destroy",
+           "hp_plan_query", "hp_plan_src_rows", "hp_plan_segments", "hp_plan_get_launch",
+           "hp_plan_set_launch", "hp_plan_tune", "hp_forward", "hp_backward",
+           "hp_set_option", "hp_get_option", "hp_profile_enable", "hp_profile_read",
+           "hp_strerror", "hp_last_hip_error", "hp_version"]
 
 _handle = None
 
@@ -79,6 +86,11 @@ def _lib():
     L.hp_plan_create.argtypes = [C.POINTER(hp_layout_t), C.POINTER(hp_layout_t),
                                  C.POINTER(hp_token_map_t), C.POINTER(vp)]
     L.hp_plan_create_host.argtypes = L.hp_plan_create.argtypes
+    L.hp_plan_create_batched.argtypes = [C.POINTER(hp_layout_t), C.POINTER(hp_layout_t),
+                                         C.POINTER(hp_token_map_t), i32, i32, C.POINTER(vp)]
+    L.hp_plan_get_launch.argtypes = [vp, i32, C.POINTER(hp_launch_t)]
+    L.hp_plan_set_launch.argtypes = [vp, i32, C.POINTER(hp_launch_t)]
+    L.hp_plan_tune.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), vp]
     L.hp_plan_destroy.argtypes = [vp]
     L.hp_plan_destroy.restype = None
     L.hp_plan_query.argtypes = [vp, C.POINTER(hp_plan_info_t)]
@@ -96,7 +108,8 @@ def _lib():
     L.hp_version.restype = C.c_char_p
     for f in ("hp_plan_create", "hp_plan_create_host", "hp_plan_query", "hp_plan_src_rows",
               "hp_plan_segments", "hp_forward", "hp_backward", "hp_set_option", "hp_last_hip_error",
-              "hp_profile_enable", "hp_profile_read"):
+              "hp_profile_enable", "hp_profile_read", "hp_plan_create_batched", "hp_plan_get_launch",
+              "hp_plan_set_launch", "hp_plan_tune"):
         getattr(L, f).restype = C.c_int
     _handle = L
     return L
@@ -161,17 +174,48 @@ class Plan:
     """Owns one hp_plan_t.  `host_only=True` builds the tables without touching
     the GPU (for inspection on machines without one)."""
 
-    def __init__(self, src: Grid, dst: Grid, tmap: TokenMap, host_only: bool = False):
+    def __init__(self, src: Grid, dst: Grid, tmap, host_only: bool = False):
         L = _lib()
         self._h = C.c_void_p(0)
-        tm, keep = _token_map(tmap)
-        fn = L.hp_plan_create_host if host_only else L.hp_plan_create
-        _check(fn(C.byref(_layout(src)), C.byref(_layout(dst)), C.byref(tm), C.byref(self._h)),
-               "hp_plan_create")
+        if isinstance(tmap, TokenMap):
+            tm, keep = _token_map(tmap)
+            fn = L.hp_plan_create_host if host_only else L.hp_plan_create
+            _check(fn(C.byref(_layout(src)), C.byref(_layout(dst)), C.byref(tm), C.byref(self._h)),
+                   "hp_plan_create")
+            self.hidden = tmap.hidden
+        else:                                   # a sequence of microbatch token maps
+            pairs = [_token_map(m) for m in tmap]
+            arr = (hp_token_map_t * len(pairs))(*[p[0] for p in pairs])
+            keep = [p[1] for p in pairs]
+            _check(L.hp_plan_create_batched(C.byref(_layout(src)), C.byref(_layout(dst)), arr, len(pairs),
+                                            1 if host_only else 0, C.byref(self._h)),
+                   "hp_plan_create_batched")
+            self.hidden = tmap[0].hidden
         del keep
         self.info = hp_plan_info_t()
         _check(L.hp_plan_query(self._h, C.byref(self.info)), "hp_plan_query")
-        self.hidden = tmap.hidden
+
+    def get_launch(self, direction: int) -> dict:
+        out = hp_launch_t()
+        _check(_lib().hp_plan_get_launch(self._h, direction, C.byref(out)), "hp_plan_get_launch")
+        return {f[0]: getattr(out, f[0]) for f in out._fields_}
+
+    def set_launch(self, direction: int, **kw) -> None:
+        cur = self.get_launch(direction)
+        cur.update(kw)
+        arg = hp_launch_t(**cur)
+        _check(_lib().hp_plan_set_launch(self._h, direction, C.byref(arg)), "hp_plan_set_launch")
+        _check(_lib().hp_plan_query(self._h, C.byref(self.info)), "hp_plan_query")
+
+    def tune(self, src_bufs=None, dst_bufs=None, dst_grad_bufs=None, src_grad_bufs=None, stream=None) -> None:
+        """Measures launch shapes on these buffers and keeps the fastest per direction."""
+        ps = pd = pgd = pgs = None
+        if src_bufs is not None:
+            ps, pd = self._src_dst(src_bufs, dst_bufs)
+        if dst_grad_bufs is not None:
+            pgs, pgd = self._src_dst(src_grad_bufs, dst_grad_bufs)
+        _check(_lib().hp_plan_tune(self._h, ps, pd, pgd, pgs, _stream_handle(stream)), "hp_plan_tune")
+        _check(_lib().hp_plan_query(self._h, C.byref(self.info)), "hp_plan_query")
 
     # -- introspection ------------------------------------------------------
     def src_rows(self) -> List[int]:
@@ -243,6 +287,15 @@ def hp_plan_create(src: Grid, dst: Grid, tmap: TokenMap) -> Plan:
 
 def hp_plan_create_host(src: Grid, dst: Grid, tmap: TokenMap) -> Plan:
     return Plan(src, dst, tmap, host_only=True)
+
+
+def hp_plan_create_batched(src: Grid, dst: Grid, tmaps: Sequence[TokenMap], host_only: bool = False) -> Plan:
+    return Plan(src, dst, list(tmaps), host_only=host_only)
+
+
+def hp_plan_tune(plan: Plan, src_bufs=None, dst_bufs=None, dst_grad_bufs=None, src_grad_bufs=None,
+                 stream=None) -> None:
+    plan.tune(src_bufs, dst_bufs, dst_grad_bufs, src_grad_bufs, stream)
 
 
 def hp_forward(plan: Plan, src_bufs, dst_bufs, stream=None) -> None:

@@ -1,16 +1,19 @@
 // C ABI and gfx950 kernels of the boundary layout transform.
 //
 // Both kernels are HBM-bound row movers (no dense contraction anywhere, so no
-// MFMA): one workgroup per tile of the plan's table, 16-byte lanes, every
-// boundary byte read exactly once (forward) or every replica byte read exactly
-// once (backward).  Forward stores each 16-byte chunk to all destination TP
-// copies from registers; backward loads the chunk from all copies, folds them
-// in binary32 in ascending tp order inside one lane (no cross-lane traffic is
-// needed because a lane owns the same eight elements of every replica), rounds
-// once to bf16 and stores to all source TP copies.
+// MFMA).  A launch cuts every segment of the plan into tiles of a few KiB and
+// runs one short-lived workgroup per tile; a workgroup finds its segment with a
+// scalar binary search over a cache-resident prefix array, then moves its tile
+// with 16-byte lanes.  Forward reads every boundary byte exactly once and
+// stores each 16-byte chunk to all destination TP copies from registers;
+// backward loads the chunk from all copies, folds them in binary32 in ascending
+// tp order inside one lane (a lane owns the same eight elements of every
+// replica, so no cross-lane traffic is needed), rounds once to bf16 and stores
+// to all source TP copies.
 #include <hip/hip_runtime.h>
 #include <hip/hip_ext.h>
 
+#include <algorithm>
 #include <cstdint>
 #include <cstring>
 #include <mutex>
@@ -37,6 +40,19 @@ struct BufTable {
     void *p[HP_MAX_BUFFERS];
 };
 
+// Everything else a kernel needs, also by value.
+struct KParams {
+    const hp::Seg *segs;        // n_seg descriptors
+    const uint32_t *first;      // n_seg + 1 tile prefix sums for this launch's tile size
+    uint32_t n_seg;
+    uint32_t tile_bytes;
+    uint32_t row_bytes;
+    uint32_t rows_per_tile;     // for row-strided segments: max(1, tile_bytes / row_bytes)
+    uint32_t dst_base;          // index of the first destination pointer in BufTable
+    uint32_t dst_copies;        // replicas of each row on the destination side
+    uint32_t src_copies;        // identical copies on the source side
+};
+
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
@@ -51,6 +67,44 @@ __device__ __forceinline__ void st(V *p, V v) {
     else *p = v;
 }
 
+// One workgroup's share of the launch.
+struct TileView {
+    uint64_t src_off, dst_off;  // bytes from the buffer bases
+    uint32_t nbytes;
+    uint32_t pitch_rows;        // 1 = dense destination
+    uint32_t src_buf, dst_buf0;
+};
+
+// Scalar code: every value here is uniform over the workgroup.
+__device__ __forceinline__ TileView locate_tile(const KParams &k, uint32_t tile) {
+    uint32_t lo = 0, hi = k.n_seg;            // first[lo] <= tile < first[hi]
+    while (hi - lo > 1) {
+        const uint32_t mid = (lo + hi) >> 1;
+        if (k.first[mid] <= tile) lo = mid; else hi = mid;
+    }
+    const hp::Seg s = k.segs[lo];
+    const uint32_t t = tile - k.first[lo];
+    TileView v;
+    v.pitch_rows = s.pitch_rows;
+    v.src_buf = s.src_buf;
+    v.dst_buf0 = s.dst_buf0;
+    if (s.pitch_rows == 1) {
+        const uint64_t off = (uint64_t)t * k.tile_bytes;
+        const uint64_t left = s.nbytes - off;
+        v.src_off = s.src_off + off;
+        v.dst_off = s.dst_off + off;
+        v.nbytes = left < k.tile_bytes ? (uint32_t)left : k.tile_bytes;
+    } else {
+        const uint64_t row0 = (uint64_t)t * k.rows_per_tile;
+        const uint64_t rows_left = s.nbytes / k.row_bytes - row0;
+        const uint32_t rows = rows_left < k.rows_per_tile ? (uint32_t)rows_left : k.rows_per_tile;
+        v.src_off = s.src_off + row0 * k.row_bytes;
+        v.dst_off = s.dst_off + row0 * s.pitch_rows * k.row_bytes;
+        v.nbytes = rows * k.row_bytes;
+    }
+    return v;
+}
+
 constexpr int kUnroll = 4;
 
 // ---------------------------------------------------------------------------
@@ -58,10 +112,9 @@ constexpr int kUnroll = 4;
 // ---------------------------------------------------------------------------
 template <typename V, int NREP, bool NTL, bool NTS>
 __global__ void __launch_bounds__(1024)
-hp_forward_kernel(const hp::Tile *__restrict__ tiles, const BufTable bufs,
-                  const uint32_t dst_base, const uint32_t row_bytes, const uint32_t nrep_rt) {
-    const hp::Tile t = tiles[blockIdx.x];
-    const uint32_t nrep = NREP > 0 ? (uint32_t)NREP : nrep_rt;
+hp_forward_kernel(const BufTable bufs, const KParams k) {
+    const TileView t = locate_tile(k, blockIdx.x);
+    const uint32_t nrep = NREP > 0 ? (uint32_t)NREP : k.dst_copies;
     const char *src = (const char *)bufs.p[t.src_buf] + t.src_off;
     const uint32_t n = t.nbytes / (uint32_t)sizeof(V);
     const uint32_t step = blockDim.x;
@@ -76,7 +129,7 @@ hp_forward_kernel(const hp::Tile *__restrict__ tiles, const BufTable bufs,
             }
 #pragma unroll 4
             for (uint32_t r = 0; r < nrep; ++r) {
-                char *dst = (char *)bufs.p[dst_base + t.dst_buf0 + r] + t.dst_off;
+                char *dst = (char *)bufs.p[k.dst_base + t.dst_buf0 + r] + t.dst_off;
 #pragma unroll
                 for (int u = 0; u < kUnroll; ++u) {
                     const uint32_t i = i0 + u * step;
@@ -86,14 +139,14 @@ hp_forward_kernel(const hp::Tile *__restrict__ tiles, const BufTable bufs,
         }
     } else {
         // row-strided destination ([S,B,H] order with several samples per rank)
-        const uint64_t pitch = (uint64_t)t.pitch_rows * row_bytes;
+        const uint64_t pitch = (uint64_t)t.pitch_rows * k.row_bytes;
         for (uint32_t i = threadIdx.x; i < n; i += step) {
             const uint32_t byte = i * (uint32_t)sizeof(V);
-            const uint32_t row = byte / row_bytes;
-            const uint32_t col = byte - row * row_bytes;
+            const uint32_t row = byte / k.row_bytes;
+            const uint32_t col = byte - row * k.row_bytes;
             const V v = ld<V, NTL>((const V *)(src + byte));
             for (uint32_t r = 0; r < nrep; ++r) {
-                char *dst = (char *)bufs.p[dst_base + t.dst_buf0 + r] + t.dst_off;
+                char *dst = (char *)bufs.p[k.dst_base + t.dst_buf0 + r] + t.dst_off;
                 st<V, NTS>((V *)(dst + row * pitch + col), v);
             }
         }
@@ -162,15 +215,13 @@ constexpr int kBwdUnroll = 2;
 
 template <int W, int NREP, bool NTL, bool NTS>
 __global__ void __launch_bounds__(1024)
-hp_backward_kernel(const hp::Tile *__restrict__ tiles, const BufTable bufs,
-                   const uint32_t dst_base, const uint32_t row_bytes,
-                   const uint32_t nrep_rt, const uint32_t src_copies) {
+hp_backward_kernel(const BufTable bufs, const KParams k) {
     typedef typename Chunk<W>::type V;
-    const hp::Tile t = tiles[blockIdx.x];
-    const uint32_t nrep = NREP > 0 ? (uint32_t)NREP : nrep_rt;
+    const TileView t = locate_tile(k, blockIdx.x);
+    const uint32_t nrep = NREP > 0 ? (uint32_t)NREP : k.dst_copies;
     const uint32_t n = t.nbytes / (uint32_t)sizeof(V);
     const uint32_t step = blockDim.x;
-    const uint64_t pitch = (uint64_t)t.pitch_rows * row_bytes;
+    const uint64_t pitch = (uint64_t)t.pitch_rows * k.row_bytes;
     const bool dense = t.pitch_rows == 1;
 
     for (uint32_t i0 = threadIdx.x; i0 < n; i0 += step * kBwdUnroll) {
@@ -182,14 +233,14 @@ hp_backward_kernel(const hp::Tile *__restrict__ tiles, const BufTable bufs,
             const uint32_t byte = i * (uint32_t)sizeof(V);
             if (dense) goff[u] = byte;
             else {
-                const uint32_t row = byte / row_bytes;
-                goff[u] = row * pitch + (byte - row * row_bytes);
+                const uint32_t row = byte / k.row_bytes;
+                goff[u] = row * pitch + (byte - row * k.row_bytes);
             }
         }
         // ascending tp: copy 0 starts the accumulator, copies 1.. are added in order
 #pragma unroll 4
         for (uint32_t r = 0; r < nrep; ++r) {
-            const char *g = (const char *)bufs.p[dst_base + t.dst_buf0 + r] + t.dst_off;
+            const char *g = (const char *)bufs.p[k.dst_base + t.dst_buf0 + r] + t.dst_off;
 #pragma unroll
             for (int u = 0; u < kBwdUnroll; ++u) {
                 const uint32_t i = i0 + u * step;
@@ -199,7 +250,7 @@ hp_backward_kernel(const hp::Tile *__restrict__ tiles, const BufTable bufs,
                 }
             }
         }
-        for (uint32_t s = 0; s < src_copies; ++s) {
+        for (uint32_t s = 0; s < k.src_copies; ++s) {
             char *out = (char *)bufs.p[t.src_buf + s] + t.src_off;
 #pragma unroll
             for (int u = 0; u < kBwdUnroll; ++u) {
@@ -213,18 +264,6 @@ hp_backward_kernel(const hp::Tile *__restrict__ tiles, const BufTable bufs,
 // ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
-
-// Largest chunk width in {16, 8, 4, 2} bytes that divides the row size and
-// every pointer the launch will touch.
-int pick_width(const hp_plan *p, const BufTable &bt, int n_ptrs) {
-    uint64_t bits = (uint64_t)p->row_bytes;
-    for (int i = 0; i < n_ptrs; ++i) bits |= (uint64_t)(uintptr_t)bt.p[i];
-    if ((bits & 15) == 0) return 16;
-    if ((bits & 7) == 0) return 8;
-    if ((bits & 3) == 0) return 4;
-    if ((bits & 1) == 0) return 2;
-    return 0;
-}
 
 // Optional per-launch kernel timing.  When enabled, every launch is given its own
 // pair of HIP events through hipExtLaunchKernelGGL, which stamps them with the
@@ -253,97 +292,139 @@ EventPair next_event_pair(int kind) {
     return e;
 }
 
-#define HP_LAUNCH(kind, kernel, grid, blk, lds, st, ...)                                        \
-    do {                                                                                        \
-        const EventPair ev_ = next_event_pair(kind);                                            \
-        hipExtLaunchKernelGGL(kernel, grid, blk, lds, st, ev_.start, ev_.stop, 0, __VA_ARGS__); \
-    } while (0)
-
+// What a launch needs beyond the kernel arguments.
 struct LaunchCfg {
-    unsigned block;      // threads per workgroup
-    unsigned lds_bytes;  // dynamic LDS requested only to cap the workgroups resident per CU
+    dim3 grid, block;
+    unsigned lds_bytes;   // dynamic LDS requested only to cap the workgroups resident per CU
+    hipStream_t stream;
+    EventPair ev;         // optional timing events for this dispatch
 };
 
-// Both kernels run fastest well below full occupancy: with every wave slot
-// busy the in-flight window of addresses is wide and HBM efficiency drops.  The
-// cap is expressed in waves per CU and enforced by requesting a slice of the
-// CU's 160 KB LDS per workgroup (the kernels do not touch it).
-LaunchCfg launch_cfg(int64_t block, int64_t waves_per_cu) {
-    LaunchCfg c{(unsigned)block, 0u};
-    const int64_t waves_per_wg = block / 64;
-    if (waves_per_cu > 0) {
-        int64_t wgs = waves_per_cu / waves_per_wg;
-        if (wgs < 2) wgs = 2;
-        if (wgs < 32) {
-            int64_t lds = (160 * 1024) / wgs - 512;
-            lds = lds / 512 * 512;
-            if (lds > 64 * 1024) lds = 64 * 1024;
-            c.lds_bytes = (unsigned)lds;
-        }
-    }
-    return c;
+#define HP_LAUNCH(kernel, c, ...) \
+    hipExtLaunchKernelGGL(kernel, (c).grid, (c).block, (c).lds_bytes, (c).stream, (c).ev.start, (c).ev.stop, 0, __VA_ARGS__)
+
+// Both kernels run fastest well below full occupancy: with every wave slot busy
+// the window of addresses in flight is wide and HBM efficiency drops.  The cap
+// is expressed in waves per CU and enforced by requesting a slice of the CU's
+// 160 KB LDS per workgroup (the kernels do not touch it).
+unsigned lds_for_cap(int block, int waves_per_cu) {
+    if (waves_per_cu <= 0) return 0;
+    int wgs = waves_per_cu / (block / 64);
+    if (wgs < 2) wgs = 2;
+    if (wgs >= 32) return 0;
+    int lds = (160 * 1024) / wgs - 512;
+    lds = lds / 512 * 512;
+    return (unsigned)std::min(lds, 64 * 1024);
+}
+
+// Largest chunk width in {16, 8, 4, 2} bytes that divides the row size and
+// every pointer the launch will touch.
+int pick_width(const hp_plan *p, const BufTable &bt, int n_ptrs) {
+    uint64_t bits = (uint64_t)p->row_bytes;
+    for (int i = 0; i < n_ptrs; ++i) bits |= (uint64_t)(uintptr_t)bt.p[i];
+    if ((bits & 15) == 0) return 16;
+    if ((bits & 7) == 0) return 8;
+    if ((bits & 3) == 0) return 4;
+    if ((bits & 1) == 0) return 2;
+    return 0;
 }
 
 template <typename V, bool NTL, bool NTS>
-void launch_forward_nrep(const hp_plan *p, const BufTable &bt, hipStream_t st, LaunchCfg c) {
-    const dim3 grid((unsigned)p->tiles.size()), blk(c.block);
-    const uint32_t base = (uint32_t)p->n_src_bufs, rb = (uint32_t)p->row_bytes, nrep = (uint32_t)p->dst_copies;
-    switch (p->dst_copies) {
-        case 1: HP_LAUNCH(0, (hp_forward_kernel<V, 1, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep); break;
-        case 2: HP_LAUNCH(0, (hp_forward_kernel<V, 2, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep); break;
-        case 4: HP_LAUNCH(0, (hp_forward_kernel<V, 4, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep); break;
-        case 8: HP_LAUNCH(0, (hp_forward_kernel<V, 8, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep); break;
-        default: HP_LAUNCH(0, (hp_forward_kernel<V, 0, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep); break;
+void launch_forward_nrep(int copies, const LaunchCfg &c, const BufTable &bt, const KParams &k) {
+    switch (copies) {
+        case 1: HP_LAUNCH((hp_forward_kernel<V, 1, NTL, NTS>), c, bt, k); break;
+        case 2: HP_LAUNCH((hp_forward_kernel<V, 2, NTL, NTS>), c, bt, k); break;
+        case 4: HP_LAUNCH((hp_forward_kernel<V, 4, NTL, NTS>), c, bt, k); break;
+        case 8: HP_LAUNCH((hp_forward_kernel<V, 8, NTL, NTS>), c, bt, k); break;
+        default: HP_LAUNCH((hp_forward_kernel<V, 0, NTL, NTS>), c, bt, k); break;
     }
 }
 
 template <bool NTL, bool NTS>
-void launch_forward(const hp_plan *p, const BufTable &bt, hipStream_t st, LaunchCfg c, int width) {
+void launch_forward_width(int width, int copies, const LaunchCfg &c, const BufTable &bt, const KParams &k) {
     switch (width) {
-        case 16: launch_forward_nrep<u32x4, NTL, NTS>(p, bt, st, c); break;
-        case 8: launch_forward_nrep<u32x2, NTL, NTS>(p, bt, st, c); break;
-        case 4: launch_forward_nrep<uint32_t, NTL, NTS>(p, bt, st, c); break;
-        default: launch_forward_nrep<uint16_t, NTL, NTS>(p, bt, st, c); break;
+        case 16: launch_forward_nrep<u32x4, NTL, NTS>(copies, c, bt, k); break;
+        case 8: launch_forward_nrep<u32x2, NTL, NTS>(copies, c, bt, k); break;
+        case 4: launch_forward_nrep<uint32_t, NTL, NTS>(copies, c, bt, k); break;
+        default: launch_forward_nrep<uint16_t, NTL, NTS>(copies, c, bt, k); break;
     }
 }
 
 template <int W, bool NTL, bool NTS>
-void launch_backward_nrep(const hp_plan *p, const BufTable &bt, hipStream_t st, LaunchCfg c) {
-    const dim3 grid((unsigned)p->tiles.size()), blk(c.block);
-    const uint32_t base = (uint32_t)p->n_src_bufs, rb = (uint32_t)p->row_bytes;
-    const uint32_t nrep = (uint32_t)p->dst_copies, sc = (uint32_t)p->src_copies;
-    switch (p->dst_copies) {
-        case 1: HP_LAUNCH(1, (hp_backward_kernel<W, 1, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep, sc); break;
-        case 2: HP_LAUNCH(1, (hp_backward_kernel<W, 2, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep, sc); break;
-        case 4: HP_LAUNCH(1, (hp_backward_kernel<W, 4, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep, sc); break;
-        case 8: HP_LAUNCH(1, (hp_backward_kernel<W, 8, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep, sc); break;
-        default: HP_LAUNCH(1, (hp_backward_kernel<W, 0, NTL, NTS>), grid, blk, c.lds_bytes, st, p->d_tiles, bt, base, rb, nrep, sc); break;
+void launch_backward_nrep(int copies, const LaunchCfg &c, const BufTable &bt, const KParams &k) {
+    switch (copies) {
+        case 1: HP_LAUNCH((hp_backward_kernel<W, 1, NTL, NTS>), c, bt, k); break;
+        case 2: HP_LAUNCH((hp_backward_kernel<W, 2, NTL, NTS>), c, bt, k); break;
+        case 4: HP_LAUNCH((hp_backward_kernel<W, 4, NTL, NTS>), c, bt, k); break;
+        case 8: HP_LAUNCH((hp_backward_kernel<W, 8, NTL, NTS>), c, bt, k); break;
+        default: HP_LAUNCH((hp_backward_kernel<W, 0, NTL, NTS>), c, bt, k); break;
     }
 }
 
 template <bool NTL, bool NTS>
-void launch_backward(const hp_plan *p, const BufTable &bt, hipStream_t st, LaunchCfg c, int width) {
+void launch_backward_width(int width, int copies, const LaunchCfg &c, const BufTable &bt, const KParams &k) {
     switch (width) {
-        case 16: launch_backward_nrep<4, NTL, NTS>(p, bt, st, c); break;
-        case 8: launch_backward_nrep<2, NTL, NTS>(p, bt, st, c); break;
-        case 4: launch_backward_nrep<1, NTL, NTS>(p, bt, st, c); break;
-        default: launch_backward_nrep<0, NTL, NTS>(p, bt, st, c); break;
+        case 16: launch_backward_nrep<4, NTL, NTS>(copies, c, bt, k); break;
+        case 8: launch_backward_nrep<2, NTL, NTS>(copies, c, bt, k); break;
+        case 4: launch_backward_nrep<1, NTL, NTS>(copies, c, bt, k); break;
+        default: launch_backward_nrep<0, NTL, NTS>(copies, c, bt, k); break;
     }
 }
 
+enum Direction { kForward = 0, kBackward = 1 };
+
+// Enqueues one kernel for direction `dir` with launch shape `L`.
+int enqueue(const hp_plan *p, Direction dir, const hp::Launch &L, const BufTable &bt, int width,
+            hipStream_t stream, EventPair ev) {
+    const size_t n_seg = p->segments.size();
+    KParams k;
+    k.segs = p->d_segs;
+    k.first = p->d_first + (size_t)L.tile_variant * (n_seg + 1);
+    k.n_seg = (uint32_t)n_seg;
+    k.tile_bytes = hp::tile_bytes_of(L.tile_variant);
+    k.row_bytes = (uint32_t)p->row_bytes;
+    k.rows_per_tile = std::max<uint32_t>(1u, k.tile_bytes / k.row_bytes);
+    k.dst_base = (uint32_t)p->n_src_bufs;
+    k.dst_copies = (uint32_t)p->dst_copies;
+    k.src_copies = (uint32_t)p->src_copies;
+    LaunchCfg c;
+    c.grid = dim3(p->n_tiles(L.tile_variant));
+    c.block = dim3((unsigned)L.block);
+    c.lds_bytes = lds_for_cap(L.block, L.waves_per_cu);
+    c.stream = stream;
+    c.ev = ev;
+    const int nt = L.nontemporal & 3, copies = p->dst_copies;
+    if (dir == kForward) {
+        switch (nt) {
+            case 0: launch_forward_width<false, false>(width, copies, c, bt, k); break;
+            case 1: launch_forward_width<true, false>(width, copies, c, bt, k); break;
+            case 2: launch_forward_width<false, true>(width, copies, c, bt, k); break;
+            default: launch_forward_width<true, true>(width, copies, c, bt, k); break;
+        }
+    } else {
+        switch (nt) {
+            case 0: launch_backward_width<false, false>(width, copies, c, bt, k); break;
+            case 1: launch_backward_width<true, false>(width, copies, c, bt, k); break;
+            case 2: launch_backward_width<false, true>(width, copies, c, bt, k); break;
+            default: launch_backward_width<true, true>(width, copies, c, bt, k); break;
+        }
+    }
+    if (hip_failed(hipGetLastError())) return HP_EHIP;
+    return HP_OK;
+}
+
 // Fills the pointer table and checks what the kernels assume: every buffer a
-// tile touches is present, and the plan's tables live on the current device.
-// `read_all_src` is false for forward (only copy tp = 0 of a source rank is
+// segment touches is present, and the plan's tables live on the current device.
+// `all_src_copies` is false for forward (only copy tp = 0 of a source rank is
 // read) and true for backward (every copy is written).
 int prepare(const hp_plan *p, const void *const *src, const void *const *dst, bool all_src_copies,
             BufTable *bt, int *width) {
     if (!p || !src || !dst) return HP_EINVAL;
-    if (!p->d_tiles && !p->tiles.empty()) return HP_ESTATE;
+    if (p->segments.empty()) return HP_OK;
+    if (!p->d_segs) return HP_ESTATE;
     int dev = -1;
-    if (!p->tiles.empty()) {
-        if (hip_failed(hipGetDevice(&dev))) return HP_EHIP;
-        if (dev != p->device) return HP_ESTATE;
-    }
+    if (hip_failed(hipGetDevice(&dev))) return HP_EHIP;
+    if (dev != p->device) return HP_ESTATE;
     std::memset(bt, 0, sizeof(*bt));
     int n = 0;
     for (int i = 0; i < p->n_src_bufs; ++i) {
@@ -352,7 +433,7 @@ int prepare(const hp_plan *p, const void *const *src, const void *const *dst, bo
         bt->p[n++] = needed ? const_cast<void *>(src[i]) : nullptr;
     }
     for (int j = 0; j < p->n_dst_bufs; ++j) {
-        if (!dst[j] && p->n_rows > 0) return HP_EINVAL;
+        if (!dst[j]) return HP_EINVAL;
         bt->p[n++] = const_cast<void *>(dst[j]);
     }
     *width = pick_width(p, *bt, n);
@@ -360,19 +441,20 @@ int prepare(const hp_plan *p, const void *const *src, const void *const *dst, bo
     return HP_OK;
 }
 
-int finish_launch() {
-    if (hip_failed(hipGetLastError())) return HP_EHIP;
-    return HP_OK;
+bool launch_ok(const hp::Launch &L) {
+    return L.tile_variant >= 0 && L.tile_variant < hp::kTileVariants && L.block >= 64 && L.block <= 1024 &&
+           L.block % 64 == 0 && L.waves_per_cu >= 0 && L.waves_per_cu <= 32 && L.nontemporal >= 0 &&
+           L.nontemporal <= 3;
 }
 
-int create_common(const hp_layout_t *src, const hp_layout_t *dst, const hp_token_map_t *map,
-                  bool upload, hp_plan_t **out) {
+int create_common(const hp_layout_t *src, const hp_layout_t *dst, const hp_token_map_t *maps,
+                  int32_t n_maps, bool upload, hp_plan_t **out) {
     if (!out) return HP_EINVAL;
     hp_plan *p = new (std::nothrow) hp_plan();
     if (!p) return HP_ENOMEM;
     int rc;
     try {
-        rc = hp::build_host_plan(src, dst, map, p);
+        rc = hp::build_host_plan(src, dst, maps, n_maps, p);
     } catch (const std::bad_alloc &) {
         rc = HP_ENOMEM;
     } catch (...) {
@@ -380,17 +462,22 @@ int create_common(const hp_layout_t *src, const hp_layout_t *dst, const hp_token
     }
     if (rc == HP_OK && upload) {
         if (hip_failed(hipGetDevice(&p->device))) rc = HP_EHIP;
-        if (rc == HP_OK && !p->tiles.empty()) {
-            const size_t bytes = p->tiles.size() * sizeof(hp::Tile);
-            hipError_t e = hipMalloc((void **)&p->d_tiles, bytes);
+        if (rc == HP_OK && !p->segments.empty()) {
+            const size_t seg_bytes = p->dsegs.size() * sizeof(hp::Seg);
+            const size_t first_bytes = p->first_tile.size() * sizeof(uint32_t);
+            hipError_t e = hipMalloc((void **)&p->d_segs, seg_bytes + first_bytes);
             if (e == hipErrorOutOfMemory) { g_last_hip_error = (int)e; rc = HP_ENOMEM; }
             else if (hip_failed(e)) rc = HP_EHIP;
-            if (rc == HP_OK && hip_failed(hipMemcpy(p->d_tiles, p->tiles.data(), bytes, hipMemcpyHostToDevice)))
-                rc = HP_EHIP;
+            if (rc == HP_OK) {
+                p->d_first = (uint32_t *)((char *)p->d_segs + seg_bytes);
+                if (hip_failed(hipMemcpy(p->d_segs, p->dsegs.data(), seg_bytes, hipMemcpyHostToDevice)) ||
+                    hip_failed(hipMemcpy(p->d_first, p->first_tile.data(), first_bytes, hipMemcpyHostToDevice)))
+                    rc = HP_EHIP;
+            }
         }
     }
     if (rc != HP_OK) {
-        if (p->d_tiles) (void)hipFree(p->d_tiles);
+        if (p->d_segs) (void)hipFree(p->d_segs);
         delete p;
         return rc;
     }
@@ -402,16 +489,72 @@ struct OptionDesc {
     const char *name;
     int64_t hp::Options::*field;
     int64_t lo, hi, multiple;
+    bool tile;
 };
 const OptionDesc kOptions[] = {
-    {"tile_bytes", &hp::Options::tile_bytes, 256, 1 << 24, 1},
-    {"block_threads_fwd", &hp::Options::block_threads_fwd, 64, 1024, 64},
-    {"block_threads_bwd", &hp::Options::block_threads_bwd, 64, 1024, 64},
-    {"nontemporal_fwd", &hp::Options::nontemporal_fwd, 0, 3, 1},
-    {"nontemporal_bwd", &hp::Options::nontemporal_bwd, 0, 3, 1},
-    {"waves_per_cu_fwd", &hp::Options::waves_per_cu_fwd, 0, 32, 1},
-    {"waves_per_cu_bwd", &hp::Options::waves_per_cu_bwd, 0, 32, 1},
+    {"tile_bytes_fwd", &hp::Options::tile_bytes_fwd, 1024, 65536, 1, true},
+    {"tile_bytes_bwd", &hp::Options::tile_bytes_bwd, 1024, 65536, 1, true},
+    {"block_threads_fwd", &hp::Options::block_threads_fwd, 64, 1024, 64, false},
+    {"block_threads_bwd", &hp::Options::block_threads_bwd, 64, 1024, 64, false},
+    {"nontemporal_fwd", &hp::Options::nontemporal_fwd, 0, 3, 1, false},
+    {"nontemporal_bwd", &hp::Options::nontemporal_bwd, 0, 3, 1, false},
+    {"waves_per_cu_fwd", &hp::Options::waves_per_cu_fwd, 0, 32, 1, false},
+    {"waves_per_cu_bwd", &hp::Options::waves_per_cu_bwd, 0, 32, 1, false},
 };
+
+// Times `reps` launches of one candidate and returns the best kernel duration
+// in milliseconds, or a negative error.
+float time_candidate(const hp_plan *p, Direction dir, const hp::Launch &L, const BufTable &bt, int width,
+                     hipStream_t stream, EventPair ev, int reps) {
+    float best = 1e30f;
+    for (int r = 0; r < reps + 1; ++r) {                    // first launch is a warm-up
+        if (enqueue(p, dir, L, bt, width, stream, ev) != HP_OK) return -1.f;
+        if (hip_failed(hipEventSynchronize(ev.stop))) return -1.f;
+        float ms = 0.f;
+        if (hip_failed(hipEventElapsedTime(&ms, ev.start, ev.stop))) return -1.f;
+        if (r > 0) best = std::min(best, ms);
+    }
+    return best;
+}
+
+// Searches the launch shapes that matter for a streaming kernel on this chip:
+// tile size x workgroup size (1, 2 or 4 sixteen-byte chunks per lane) x the
+// resident-wave cap.  Keeps the plan's cache policy.
+int tune_direction(hp_plan *p, Direction dir, const BufTable &bt, int width, hipStream_t stream) {
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    if (hip_failed(hipEventCreate(&e0))) return HP_EHIP;
+    if (hip_failed(hipEventCreate(&e1))) { (void)hipEventDestroy(e0); return HP_EHIP; }
+    const EventPair ev{e0, e1};
+    hp::Launch &cur = dir == kForward ? p->fwd : p->bwd;
+    hp::Launch best = cur;
+    float best_ms = time_candidate(p, dir, cur, bt, width, stream, ev, 3);
+    int rc = best_ms < 0 ? HP_EHIP : HP_OK;
+    const int blocks[] = {64, 128, 256};
+    const int caps[] = {4, 6, 8, 12, 16, 24, 0};
+    for (int v = 0; v <= 3 && rc == HP_OK; ++v) {                       // 1, 2, 4, 8 KiB tiles
+        for (int b : blocks) {
+            const int chunks = (int)(hp::tile_bytes_of(v) / 16u) / b;   // 16-byte chunks per lane
+            if (chunks != 1 && chunks != 2 && chunks != 4) continue;
+            for (int cap : caps) {
+                if (cap && cap < 2 * (b / 64)) continue;                // cap below two workgroups
+                hp::Launch L{v, b, cap, cur.nontemporal};
+                const float ms = time_candidate(p, dir, L, bt, width, stream, ev, 2);
+                if (ms < 0) { rc = HP_EHIP; break; }
+                if (ms < best_ms) { best_ms = ms; best = L; }
+            }
+            if (rc != HP_OK) break;
+        }
+    }
+    if (rc == HP_OK) {
+        // confirm the winner against the runner-up noise: re-time it with more repetitions
+        const float again = time_candidate(p, dir, best, bt, width, stream, ev, 5);
+        if (again < 0) rc = HP_EHIP;
+        else cur = best;
+    }
+    (void)hipEventDestroy(e0);
+    (void)hipEventDestroy(e1);
+    return rc;
+}
 
 }  // namespace
 
@@ -419,17 +562,22 @@ extern "C" {
 
 int hp_plan_create(const hp_layout_t *src, const hp_layout_t *dst, const hp_token_map_t *map,
                    hp_plan_t **out) {
-    return create_common(src, dst, map, true, out);
+    return create_common(src, dst, map, 1, true, out);
 }
 
 int hp_plan_create_host(const hp_layout_t *src, const hp_layout_t *dst, const hp_token_map_t *map,
                         hp_plan_t **out) {
-    return create_common(src, dst, map, false, out);
+    return create_common(src, dst, map, 1, false, out);
+}
+
+int hp_plan_create_batched(const hp_layout_t *src, const hp_layout_t *dst, const hp_token_map_t *maps,
+                           int32_t n_maps, int32_t host_only, hp_plan_t **out) {
+    return create_common(src, dst, maps, n_maps, host_only == 0, out);
 }
 
 void hp_plan_destroy(hp_plan_t *plan) {
     if (!plan) return;
-    if (plan->d_tiles) (void)hipFree(plan->d_tiles);
+    if (plan->d_segs) (void)hipFree(plan->d_segs);
     delete plan;
 }
 
@@ -448,9 +596,10 @@ int hp_plan_query(const hp_plan_t *p, hp_plan_info_t *info) {
     o.fwd_bytes = (1 + (int64_t)p->dst_copies) * o.boundary_bytes;
     o.bwd_bytes = ((int64_t)p->dst_copies + p->src_copies) * o.boundary_bytes;
     o.n_segments = (int32_t)p->segments.size();
-    o.n_tiles = (int32_t)p->tiles.size();
-    o.on_device = (p->d_tiles != nullptr || (p->device >= 0 && p->tiles.empty())) ? 1 : 0;
+    o.n_tiles = (int32_t)p->n_tiles(p->fwd.tile_variant);
+    o.on_device = (p->d_segs != nullptr || (p->device >= 0 && p->segments.empty())) ? 1 : 0;
     o.device = p->device;
+    o.n_maps = p->n_maps;
     *info = o;
     return HP_OK;
 }
@@ -468,20 +617,30 @@ int hp_plan_segments(const hp_plan_t *p, hp_segment_t *out, int32_t cap) {
     return n;
 }
 
+int hp_plan_get_launch(const hp_plan_t *p, int32_t direction, hp_launch_t *out) {
+    if (!p || !out || (direction != 0 && direction != 1)) return HP_EINVAL;
+    const hp::Launch &L = direction == 0 ? p->fwd : p->bwd;
+    out->tile_bytes = (int32_t)hp::tile_bytes_of(L.tile_variant);
+    out->block_threads = L.block;
+    out->waves_per_cu = L.waves_per_cu;
+    out->nontemporal = L.nontemporal;
+    return HP_OK;
+}
+
+int hp_plan_set_launch(hp_plan_t *p, int32_t direction, const hp_launch_t *in) {
+    if (!p || !in || (direction != 0 && direction != 1)) return HP_EINVAL;
+    hp::Launch L{hp::tile_variant_of(in->tile_bytes), in->block_threads, in->waves_per_cu, in->nontemporal};
+    if (!launch_ok(L)) return HP_EINVAL;
+    (direction == 0 ? p->fwd : p->bwd) = L;
+    return HP_OK;
+}
+
 int hp_forward(const hp_plan_t *p, const void *const *src_bufs, void *const *dst_bufs, void *stream) {
     BufTable bt;
     int width = 0;
     int rc = prepare(p, src_bufs, (const void *const *)dst_bufs, false, &bt, &width);
-    if (rc != HP_OK) return rc;
-    if (p->tiles.empty()) return HP_OK;
-    const LaunchCfg block = launch_cfg(hp::options().block_threads_fwd, hp::options().waves_per_cu_fwd);
-    switch (hp::options().nontemporal_fwd & 3) {
-        case 0: launch_forward<false, false>(p, bt, (hipStream_t)stream, block, width); break;
-        case 1: launch_forward<true, false>(p, bt, (hipStream_t)stream, block, width); break;
-        case 2: launch_forward<false, true>(p, bt, (hipStream_t)stream, block, width); break;
-        default: launch_forward<true, true>(p, bt, (hipStream_t)stream, block, width); break;
-    }
-    return finish_launch();
+    if (rc != HP_OK || p->segments.empty()) return rc;
+    return enqueue(p, kForward, p->fwd, bt, width, (hipStream_t)stream, next_event_pair(0));
 }
 
 int hp_backward(const hp_plan_t *p, const void *const *dst_grad_bufs, void *const *src_grad_bufs,
@@ -489,16 +648,27 @@ int hp_backward(const hp_plan_t *p, const void *const *dst_grad_bufs, void *cons
     BufTable bt;
     int width = 0;
     int rc = prepare(p, (const void *const *)src_grad_bufs, dst_grad_bufs, true, &bt, &width);
-    if (rc != HP_OK) return rc;
-    if (p->tiles.empty()) return HP_OK;
-    const LaunchCfg block = launch_cfg(hp::options().block_threads_bwd, hp::options().waves_per_cu_bwd);
-    switch (hp::options().nontemporal_bwd & 3) {
-        case 0: launch_backward<false, false>(p, bt, (hipStream_t)stream, block, width); break;
-        case 1: launch_backward<true, false>(p, bt, (hipStream_t)stream, block, width); break;
-        case 2: launch_backward<false, true>(p, bt, (hipStream_t)stream, block, width); break;
-        default: launch_backward<true, true>(p, bt, (hipStream_t)stream, block, width); break;
+    if (rc != HP_OK || p->segments.empty()) return rc;
+    return enqueue(p, kBackward, p->bwd, bt, width, (hipStream_t)stream, next_event_pair(1));
+}
+
+int hp_plan_tune(hp_plan_t *p, const void *const *src_bufs, void *const *dst_bufs,
+                 const void *const *dst_grad_bufs, void *const *src_grad_bufs, void *stream) {
+    if (!p) return HP_EINVAL;
+    if ((src_bufs == nullptr) != (dst_bufs == nullptr)) return HP_EINVAL;
+    if ((dst_grad_bufs == nullptr) != (src_grad_bufs == nullptr)) return HP_EINVAL;
+    if (p->segments.empty()) return HP_OK;
+    BufTable bt;
+    int width = 0, rc = HP_OK;
+    if (src_bufs) {
+        rc = prepare(p, src_bufs, (const void *const *)dst_bufs, false, &bt, &width);
+        if (rc == HP_OK) rc = tune_direction(p, kForward, bt, width, (hipStream_t)stream);
     }
-    return finish_launch();
+    if (rc == HP_OK && dst_grad_bufs) {
+        rc = prepare(p, (const void *const *)src_grad_bufs, dst_grad_bufs, true, &bt, &width);
+        if (rc == HP_OK) rc = tune_direction(p, kBackward, bt, width, (hipStream_t)stream);
+    }
+    return rc;
 }
 
 int hp_set_option(const char *key, int64_t value) {
@@ -506,6 +676,7 @@ int hp_set_option(const char *key, int64_t value) {
     for (const OptionDesc &d : kOptions) {
         if (std::strcmp(key, d.name)) continue;
         if (value < d.lo || value > d.hi || (d.multiple > 1 && value % d.multiple)) return HP_EINVAL;
+        if (d.tile && hp::tile_variant_of(value) < 0) return HP_EINVAL;
         hp::options().*(d.field) = value;
         return HP_OK;
     }
@@ -580,6 +751,6 @@ const char *hp_strerror(int code) {
 
 int hp_last_hip_error(void) { return g_last_hip_error; }
 
-const char *hp_version(void) { return "hp-boundary 0.1 (gfx950)"; }
+const char *hp_version(void) { return "hp-boundary 0.2 (gfx950)"; }
 
 }  // extern "C"

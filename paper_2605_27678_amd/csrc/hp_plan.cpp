@@ -1,5 +1,5 @@
-// Host-side plan builder: turns two module grids and a token map into the
-// segment and tile tables the gfx950 kernels consume.  Pure C++, no HIP calls.
+// Host-side plan builder: turns two module grids and one or more token maps
+// into the segment tables the gfx950 kernels consume.  Pure C++, no HIP calls.
 //
 // The step it implements is the one the paper describes for communicator
 // construction (Colocated communicator, second paragraph: derive every rank's
@@ -21,6 +21,12 @@ namespace hp {
 Options &options() {
     static Options o;
     return o;
+}
+
+int tile_variant_of(int64_t tile_bytes) {
+    for (int v = 0; v < kTileVariants; ++v)
+        if (tile_bytes == (int64_t)tile_bytes_of(v)) return v;
+    return -1;
 }
 
 namespace {
@@ -75,7 +81,7 @@ struct DstWalker {
     }
 };
 
-int validate(const hp_layout_t *src, const hp_layout_t *dst, const hp_token_map_t *m) {
+int validate(const hp_layout_t *src, const hp_layout_t *dst, const hp_token_map_t *m, int32_t n_maps) {
     if (!src || !dst || !m) return HP_EINVAL;
     for (const hp_layout_t *g : {src, dst}) {
         if (g->tp < 1 || g->cp < 1 || g->dp < 1 || g->pp < 1 || g->rank_offset < 0) return HP_EINVAL;
@@ -95,7 +101,7 @@ int validate(const hp_layout_t *src, const hp_layout_t *dst, const hp_token_map_
     if (dst->tp_mode == HP_TP_SEQ_SHARD && (m->seq / dst->cp) % dst->tp) return HP_ELAYOUT;
     int64_t n_src = (int64_t)src->tp * src->dp;
     int64_t n_dst = (int64_t)dst->tp * dst->cp * dst->dp;
-    if (n_src + n_dst > HP_MAX_BUFFERS) return HP_ELAYOUT;
+    if ((n_src + n_dst) * n_maps > HP_MAX_BUFFERS) return HP_ELAYOUT;
     if (dst->tp_mode == HP_TP_REPLICATE && dst->tp > HP_MAX_TP) return HP_ELAYOUT;
 
     // spans
@@ -128,115 +134,134 @@ int validate(const hp_layout_t *src, const hp_layout_t *dst, const hp_token_map_
     return HP_OK;
 }
 
-void make_tiles(hp_plan *p) {
-    const int64_t rb = p->row_bytes;
-    int64_t tile = std::max<int64_t>(256, options().tile_bytes / 256 * 256);
-    p->tiles.clear();
-    for (const hp_segment_t &s : p->segments) {
-        const uint64_t src0 = (uint64_t)s.src_row0 * rb, dst0 = (uint64_t)s.dst_row0 * rb;
-        if (s.dst_row_stride == 1) {
-            const int64_t total = s.n_rows * rb;
-            for (int64_t o = 0; o < total; o += tile) {
-                Tile t{};
-                t.src_off = src0 + o;
-                t.dst_off = dst0 + o;
-                t.nbytes = (uint32_t)std::min<int64_t>(tile, total - o);
-                t.pitch_rows = 1;
-                t.src_buf = (uint16_t)s.src_buf;
-                t.dst_buf0 = (uint16_t)s.dst_buf0;
-                p->tiles.push_back(t);
-            }
-        } else {
-            const int64_t rows_per = std::max<int64_t>(1, tile / rb);
-            for (int64_t r = 0; r < s.n_rows; r += rows_per) {
-                Tile t{};
-                t.src_off = src0 + (uint64_t)r * rb;
-                t.dst_off = dst0 + (uint64_t)r * s.dst_row_stride * rb;
-                t.nbytes = (uint32_t)(std::min<int64_t>(rows_per, s.n_rows - r) * rb);
-                t.pitch_rows = (uint32_t)s.dst_row_stride;
-                t.src_buf = (uint16_t)s.src_buf;
-                t.dst_buf0 = (uint16_t)s.dst_buf0;
-                p->tiles.push_back(t);
-            }
-        }
+// Tiles of `tile` bytes needed by a segment: dense segments are cut by bytes,
+// row-strided ones by whole rows.  The kernels use the same two formulas.
+uint64_t tiles_of(const hp_segment_t &s, int64_t row_bytes, uint32_t tile) {
+    if (s.dst_row_stride == 1) return ((uint64_t)s.n_rows * row_bytes + tile - 1) / tile;
+    const uint64_t rows_per = std::max<uint64_t>(1, tile / (uint64_t)row_bytes);
+    return ((uint64_t)s.n_rows + rows_per - 1) / rows_per;
+}
+
+int make_tables(hp_plan *p) {
+    const size_t n = p->segments.size();
+    p->dsegs.resize(n);
+    for (size_t i = 0; i < n; ++i) {
+        const hp_segment_t &s = p->segments[i];
+        Seg &d = p->dsegs[i];
+        d.src_off = (uint64_t)s.src_row0 * p->row_bytes;
+        d.dst_off = (uint64_t)s.dst_row0 * p->row_bytes;
+        d.nbytes = (uint64_t)s.n_rows * p->row_bytes;
+        d.pitch_rows = (uint32_t)s.dst_row_stride;
+        d.src_buf = (uint16_t)s.src_buf;
+        d.dst_buf0 = (uint16_t)s.dst_buf0;
     }
+    p->first_tile.assign((size_t)kTileVariants * (n + 1), 0u);
+    for (int v = 0; v < kTileVariants; ++v) {
+        uint64_t acc = 0;
+        uint32_t *row = p->first_tile.data() + (size_t)v * (n + 1);
+        for (size_t i = 0; i < n; ++i) {
+            row[i] = (uint32_t)acc;
+            acc += tiles_of(p->segments[i], p->row_bytes, tile_bytes_of(v));
+            if (acc > 0x7fffffffull) return HP_ELAYOUT;        // grid size limit
+        }
+        row[n] = (uint32_t)acc;
+    }
+    return HP_OK;
 }
 
 }  // namespace
 
 int build_host_plan(const hp_layout_t *src, const hp_layout_t *dst,
-                    const hp_token_map_t *m, hp_plan *p) {
-    int rc = validate(src, dst, m);
-    if (rc != HP_OK) return rc;
+                    const hp_token_map_t *maps, int32_t n_maps, hp_plan *p) {
+    if (!maps || n_maps < 1) return HP_EINVAL;
+    for (int32_t i = 0; i < n_maps; ++i) {
+        int rc = validate(src, dst, &maps[i], n_maps);
+        if (rc != HP_OK) return rc;
+        // microbatches share the buffer shapes
+        if (maps[i].batch != maps[0].batch || maps[i].seq != maps[0].seq ||
+            maps[i].hidden != maps[0].hidden || maps[i].dtype != maps[0].dtype)
+            return HP_ELAYOUT;
+    }
+    const hp_token_map_t *m0 = &maps[0];
 
     p->src = *src;
     p->dst = *dst;
-    p->batch = m->batch; p->seq = m->seq; p->hidden = m->hidden; p->dtype = m->dtype;
+    p->batch = m0->batch; p->seq = m0->seq; p->hidden = m0->hidden; p->dtype = m0->dtype;
+    p->n_maps = n_maps;
     p->elem_bytes = 2;
-    p->row_bytes = (int64_t)m->hidden * p->elem_bytes;
+    p->row_bytes = (int64_t)m0->hidden * p->elem_bytes;
     if (p->row_bytes > (int64_t)1 << 24) return HP_ELAYOUT;       // a tile holds whole rows in 32 bits
-    p->n_src_bufs = src->tp * src->dp;
-    p->n_dst_bufs = dst->tp * dst->cp * dst->dp;
+    const int32_t src_per_map = src->tp * src->dp;
+    const int32_t dst_per_map = dst->tp * dst->cp * dst->dp;
+    p->n_src_bufs = src_per_map * n_maps;
+    p->n_dst_bufs = dst_per_map * n_maps;
     p->src_copies = src->tp;
     p->dst_copies = dst->tp_mode == HP_TP_SEQ_SHARD ? 1 : dst->tp;
 
-    const DstWalker walk(*dst, m->seq);
-    const int64_t b_loc = m->batch / dst->dp;                      // samples per destination dp rank
+    const DstWalker walk(*dst, m0->seq);
+    const int64_t b_loc = m0->batch / dst->dp;                     // samples per destination dp rank
     p->dst_rows_per_buf = b_loc * walk.piece;
     const bool sbh = dst->row_order == HP_ROW_SBH;
     const int64_t stride = (sbh && b_loc > 1) ? b_loc : 1;
 
-    // source side: each dp rank's buffer fills up in global image order
-    std::vector<int64_t> fill(src->dp, 0);
-    const int64_t K = m->n_images;
-    int32_t d = 0;
     p->n_rows = 0;
     p->segments.clear();
-    for (int64_t k = 0; k < K; ++k) {
-        if (m->img_src_dp) {
-            d = m->img_src_dp[k];
-        } else {
-            while (k >= ((int64_t)(d + 1) * K) / src->dp) ++d;    // next balanced interval
-        }
-        const int32_t b = m->img_sample[k];
-        const int32_t dpd = (int32_t)(b / b_loc);
-        const int64_t bl = b - (int64_t)dpd * b_loc;
-        int64_t s = m->img_start[k], left = m->img_len[k];
-        while (left > 0) {
-            const DstPos pos = walk.at(dpd, s);
-            const int64_t n = std::min(left, pos.run);
-            hp_segment_t seg;
-            seg.src_buf = d * src->tp;
-            seg.dst_buf0 = pos.buf0;
-            seg.src_row0 = fill[d];
-            seg.dst_row0 = sbh ? pos.s_loc * b_loc + bl : bl * walk.piece + pos.s_loc;
-            seg.n_rows = n;
-            seg.dst_row_stride = stride;
-            bool merged = false;
-            if (!p->segments.empty()) {
-                hp_segment_t &q = p->segments.back();
-                if (q.src_buf == seg.src_buf && q.dst_buf0 == seg.dst_buf0 &&
-                    q.dst_row_stride == seg.dst_row_stride &&
-                    q.src_row0 + q.n_rows == seg.src_row0 &&
-                    q.dst_row0 + q.n_rows * q.dst_row_stride == seg.dst_row0) {
-                    q.n_rows += n;
-                    merged = true;
-                }
-            }
-            if (!merged) p->segments.push_back(seg);
-            fill[d] += n;
-            p->n_rows += n;
-            s += n;
-            left -= n;
-        }
-    }
     p->src_rows.assign(p->n_src_bufs, 0);
-    for (int32_t dd = 0; dd < src->dp; ++dd)
-        for (int32_t t = 0; t < src->tp; ++t) p->src_rows[t + src->tp * dd] = fill[dd];
+    for (int32_t mi = 0; mi < n_maps; ++mi) {
+        const hp_token_map_t *m = &maps[mi];
+        const int32_t src_base = mi * src_per_map, dst_base = mi * dst_per_map;
+        // source side: each dp rank's buffer fills up in global image order
+        std::vector<int64_t> fill(src->dp, 0);
+        const int64_t K = m->n_images;
+        int32_t d = 0;
+        for (int64_t k = 0; k < K; ++k) {
+            if (m->img_src_dp) {
+                d = m->img_src_dp[k];
+            } else {
+                while (k >= ((int64_t)(d + 1) * K) / src->dp) ++d;    // next balanced interval
+            }
+            const int32_t b = m->img_sample[k];
+            const int32_t dpd = (int32_t)(b / b_loc);
+            const int64_t bl = b - (int64_t)dpd * b_loc;
+            int64_t s = m->img_start[k], left = m->img_len[k];
+            while (left > 0) {
+                const DstPos pos = walk.at(dpd, s);
+                const int64_t n = std::min(left, pos.run);
+                hp_segment_t seg;
+                seg.src_buf = src_base + d * src->tp;
+                seg.dst_buf0 = dst_base + pos.buf0;
+                seg.src_row0 = fill[d];
+                seg.dst_row0 = sbh ? pos.s_loc * b_loc + bl : bl * walk.piece + pos.s_loc;
+                seg.n_rows = n;
+                seg.dst_row_stride = stride;
+                bool merged = false;
+                if (!p->segments.empty()) {
+                    hp_segment_t &q = p->segments.back();
+                    if (q.src_buf == seg.src_buf && q.dst_buf0 == seg.dst_buf0 &&
+                        q.dst_row_stride == seg.dst_row_stride &&
+                        q.src_row0 + q.n_rows == seg.src_row0 &&
+                        q.dst_row0 + q.n_rows * q.dst_row_stride == seg.dst_row0) {
+                        q.n_rows += n;
+                        merged = true;
+                    }
+                }
+                if (!merged) p->segments.push_back(seg);
+                fill[d] += n;
+                p->n_rows += n;
+                s += n;
+                left -= n;
+            }
+        }
+        for (int32_t dd = 0; dd < src->dp; ++dd)
+            for (int32_t t = 0; t < src->tp; ++t) p->src_rows[src_base + t + src->tp * dd] = fill[dd];
+    }
 
-    make_tiles(p);
-    if (p->tiles.size() > (size_t)std::numeric_limits<int32_t>::max()) return HP_ELAYOUT;
-    return HP_OK;
+    const Options &o = options();
+    p->fwd = Launch{tile_variant_of(o.tile_bytes_fwd), (int32_t)o.block_threads_fwd,
+                    (int32_t)o.waves_per_cu_fwd, (int32_t)o.nontemporal_fwd};
+    p->bwd = Launch{tile_variant_of(o.tile_bytes_bwd), (int32_t)o.block_threads_bwd,
+                    (int32_t)o.waves_per_cu_bwd, (int32_t)o.nontemporal_bwd};
+    return make_tables(p);
 }
 
 }  // namespace hp

@@ -7,53 +7,78 @@
 
 namespace hp {
 
-// One workgroup's share of a launch: a byte range that is contiguous in the
-// source buffer and either contiguous (pitch_rows == 1) or row-strided in the
-// destination buffer(s).  32 bytes, read with scalar loads.
-struct alignas(16) Tile {
+// Device-side descriptor of one segment: a run of image-token rows that is
+// contiguous in its source buffer and contiguous (pitch_rows == 1) or evenly
+// row-strided in each destination copy.  32 bytes; the whole table of a plan is
+// a few KB and stays hot in the scalar cache.
+struct alignas(16) Seg {
     uint64_t src_off;     // bytes from the base of the source buffer
     uint64_t dst_off;     // bytes from the base of each destination copy
-    uint32_t nbytes;      // payload bytes; whole rows when pitch_rows != 1
+    uint64_t nbytes;      // rows * row_bytes
     uint32_t pitch_rows;  // destination row pitch in rows (1 = dense)
     uint16_t src_buf;     // source buffer index of copy tp = 0
     uint16_t dst_buf0;    // first destination buffer index
-    uint32_t reserved;
 };
-static_assert(sizeof(Tile) == 32, "tile table entry must stay 32 bytes");
+static_assert(sizeof(Seg) == 32, "segment descriptor must stay 32 bytes");
+
+// A launch cuts every segment into tiles of 1 KiB << v bytes, one workgroup per
+// tile.  For each variant v the plan keeps first_tile[v][s] = number of tiles of
+// segments 0..s-1, so a workgroup finds its segment by a binary search over a
+// tiny, cache-resident array instead of reading a per-tile table from HBM.
+constexpr int kTileVariants = 7;
+inline uint32_t tile_bytes_of(int v) { return 1024u << v; }
+
+// How one direction is launched.  Lives in the plan; seeded from the
+// process-wide defaults, overridden by hp_plan_set_launch or hp_plan_tune.
+struct Launch {
+    int32_t tile_variant;   // tile = 1 KiB << tile_variant
+    int32_t block;          // threads per workgroup
+    int32_t waves_per_cu;   // resident-wave cap, 0 = none
+    int32_t nontemporal;    // bit 0 streaming loads, bit 1 streaming stores
+};
 
 struct Options {
-    int64_t tile_bytes = 8192;
-    int64_t block_threads_fwd = 256;
-    int64_t block_threads_bwd = 256;
-    int64_t waves_per_cu_fwd = 8;   // 0 = no cap
-    int64_t waves_per_cu_bwd = 12;
-    int64_t nontemporal_fwd = 2;  // bit 0: streaming loads, bit 1: streaming stores
-    int64_t nontemporal_bwd = 3;
+    int64_t tile_bytes_fwd = 4096, tile_bytes_bwd = 4096;
+    int64_t block_threads_fwd = 256, block_threads_bwd = 256;
+    int64_t waves_per_cu_fwd = 16, waves_per_cu_bwd = 16;   // 0 = no cap
+    int64_t nontemporal_fwd = 2, nontemporal_bwd = 3;       // bit 0 loads, bit 1 stores
 };
 Options &options();
+int tile_variant_of(int64_t tile_bytes);   // -1 unless 1 KiB << v, v < kTileVariants
 
 }  // namespace hp
 
 struct hp_plan {
     hp_layout_t src{}, dst{};
     int32_t batch = 0, seq = 0, hidden = 0, dtype = 0;
+    int32_t n_maps = 1;                   // microbatches folded into this plan
     int32_t elem_bytes = 2;
     int64_t row_bytes = 0;
     int64_t n_rows = 0;
-    int32_t n_src_bufs = 0, n_dst_bufs = 0;
+    int32_t n_src_bufs = 0, n_dst_bufs = 0;   // totals over all microbatches
     int32_t src_copies = 1, dst_copies = 1;
     int64_t dst_rows_per_buf = 0;
     std::vector<int64_t> src_rows;        // per source buffer
-    std::vector<hp_segment_t> segments;
-    std::vector<hp::Tile> tiles;
+    std::vector<hp_segment_t> segments;   // public view (rows)
+    std::vector<hp::Seg> dsegs;           // device view (bytes)
+    std::vector<uint32_t> first_tile;     // kTileVariants x (n_segments + 1), row-major
+    hp::Launch fwd{}, bwd{};
     // device side
-    hp::Tile *d_tiles = nullptr;
+    hp::Seg *d_segs = nullptr;
+    uint32_t *d_first = nullptr;
     int device = -1;
+
+    uint32_t n_tiles(int variant) const {
+        const size_t n = segments.size();
+        return n ? first_tile[(size_t)variant * (n + 1) + n] : 0u;
+    }
 };
 
 namespace hp {
-// Validates and fills everything except the device fields.  Returns HP_OK or a
-// negative error; *plan is only meaningful on HP_OK.
+// Validates and fills everything except the device fields for `n_maps` token
+// maps that share the two grids (buffers of microbatch m follow those of
+// microbatch m-1 on both sides).  Returns HP_OK or a negative error; *plan is
+// only meaningful on HP_OK.
 int build_host_plan(const hp_layout_t *src, const hp_layout_t *dst,
-                    const hp_token_map_t *map, hp_plan *plan);
+                    const hp_token_map_t *maps, int32_t n_maps, hp_plan *plan);
 }  // namespace hp

@@ -15,11 +15,13 @@ from parity import _to_host_bits, check_case
 
 pytestmark = pytest.mark.gpu
 
+OPTION_KEYS = ("tile_bytes_fwd", "tile_bytes_bwd", "block_threads_fwd", "block_threads_bwd",
+               "nontemporal_fwd", "nontemporal_bwd", "waves_per_cu_fwd", "waves_per_cu_bwd")
+
 
 @pytest.fixture(autouse=True)
 def _default_options():
-    saved = {k: hp.hp_get_option(k) for k in ("tile_bytes", "block_threads_fwd", "block_threads_bwd", "nontemporal_fwd", "nontemporal_bwd",
-                                             "waves_per_cu_fwd", "waves_per_cu_bwd")}
+    saved = {k: hp.hp_get_option(k) for k in OPTION_KEYS}
     yield
     for k, v in saved.items():
         hp.hp_set_option(k, v)
@@ -49,17 +51,19 @@ def test_long_context_spans_at_several_hidden_sizes(hidden):
     2/4/8/16-byte lane paths and many tiles per segment."""
     w = wl.long_context(n_images=9)
     tm = replace(w.maps[0], hidden=hidden)
-    hp.hp_set_option("tile_bytes", 4096)
+    hp.hp_set_option("tile_bytes_fwd", 1024)
+    hp.hp_set_option("tile_bytes_bwd", 2048)
     check_case(w.src, w.dst, tm, seed=hidden)
 
 
-@pytest.mark.parametrize("tile,block,nt,waves", [(256, 64, 1, 0), (1024, 128, 0, 4), (32768, 256, 2, 8),
-                                                (65536, 512, 3, 16), (1 << 20, 1024, 1, 32),
-                                                (4096, 256, 2, 12), (2048, 64, 3, 1)])
+@pytest.mark.parametrize("tile,block,nt,waves", [(1024, 64, 1, 0), (1024, 128, 0, 4), (32768, 256, 2, 8),
+                                                (65536, 512, 3, 16), (16384, 1024, 1, 32),
+                                                (4096, 256, 2, 12), (2048, 64, 3, 1), (8192, 192, 0, 6)])
 def test_launch_shapes(tile, block, nt, waves):
-    hp.hp_set_option("tile_bytes", tile)
+    hp.hp_set_option("tile_bytes_fwd", tile)
+    hp.hp_set_option("tile_bytes_bwd", (1 << 26) // tile)          # 64 KiB .. 1 KiB, the other way round
     hp.hp_set_option("block_threads_fwd", block)
-    hp.hp_set_option("block_threads_bwd", 1024 // (block // 64))
+    hp.hp_set_option("block_threads_bwd", 64 * (16 // (block // 64)))
     hp.hp_set_option("waves_per_cu_fwd", waves)
     hp.hp_set_option("waves_per_cu_bwd", 32 - waves)
     hp.hp_set_option("nontemporal_fwd", nt)
@@ -250,3 +254,78 @@ def test_full_large_scale():
     w = wl.large_scale()
     info = check_case(w.src, w.dst, w.maps[0], seed=5, gen_device="cuda")
     assert (info.src_copies, info.dst_copies) == (2, 8)
+
+
+# ---- batched plans and the tuner ------------------------------------------------
+
+def _batched_case(w, hidden, seed):
+    """One batched plan over all microbatches vs the oracle run per microbatch."""
+    maps = [replace(m, hidden=hidden) for m in w.maps]
+    plan = hp.hp_plan_create_batched(w.src, w.dst, maps)
+    n_src, n_dst = w.src.n_ranks, w.dst.n_ranks
+    rows, drows = plan.src_rows(), plan.info.dst_rows_per_buf
+    src = [wl.random_bf16((r, hidden), seed * 977 + i, "cuda") for i, r in enumerate(rows)]
+    dst = [wl.random_bf16((drows, hidden), seed * 977 + 400 + j, "cuda") for j in range(plan.info.n_dst_bufs)]
+    grad = [wl.random_bf16((drows, hidden), seed * 977 + 800 + j, "cuda") for j in range(plan.info.n_dst_bufs)]
+    pre = [_to_host_bits(t).copy() for t in dst]
+    sg = [torch.full((r, hidden), 7.0, dtype=torch.bfloat16, device="cuda") for r in rows]
+    st = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    hp.hp_forward(plan, src, dst, st)
+    hp.hp_backward(plan, grad, sg, st)
+    st.synchronize()
+    for mi, tm in enumerate(maps):
+        prob = oracle.Problem(w.src, w.dst, tm)
+        o_dst = pre[mi * n_dst:(mi + 1) * n_dst]
+        prob.forward([_to_host_bits(t) for t in src[mi * n_src:(mi + 1) * n_src]], o_dst)
+        for j in range(n_dst):
+            assert np.array_equal(_to_host_bits(dst[mi * n_dst + j]), o_dst[j]), (mi, j)
+        o_sg = [np.zeros((r, hidden), np.uint16) for r in prob.src_rows()]
+        prob.backward_bf16([_to_host_bits(t) for t in grad[mi * n_dst:(mi + 1) * n_dst]], o_sg)
+        for i in range(n_src):
+            assert np.array_equal(_to_host_bits(sg[mi * n_src + i]), o_sg[i]), (mi, i)
+    return plan
+
+
+def test_batched_plan_small():
+    _batched_case(wl.non_colocated(n_microbatches=5), 72, seed=1)
+
+
+def test_batched_plan_full_non_colocated():
+    """All 16 microbatches of config 4 at full size in one launch per direction."""
+    plan = _batched_case(wl.non_colocated(), 8192, seed=2)
+    assert plan.info.n_maps == 16 and plan.info.n_src_bufs == 64 and plan.info.n_dst_bufs == 64
+
+
+def test_tune_keeps_results_exact_and_picks_a_valid_shape():
+    w = wl.scaled(wl.long_context(), 1024)
+    tm = w.maps[0]
+    plan = hp.hp_plan_create(w.src, w.dst, tm)
+    prob = oracle.Problem(w.src, w.dst, tm)
+    rows, drows = plan.src_rows(), plan.info.dst_rows_per_buf
+    src = [wl.random_bf16((r, 1024), 5 + i, "cuda") for i, r in enumerate(rows)]
+    dst = [wl.random_bf16((drows, 1024), 50 + j, "cuda") for j in range(32)]
+    grad = [wl.random_bf16((drows, 1024), 90 + j, "cuda") for j in range(32)]
+    pre = [_to_host_bits(t).copy() for t in dst]
+    sg = [torch.zeros((r, 1024), dtype=torch.bfloat16, device="cuda") for r in rows]
+    st = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    hp.hp_plan_tune(plan, src, dst, grad, sg, st)
+    for d in (0, 1):
+        L = plan.get_launch(d)
+        assert L["tile_bytes"] in (1024, 2048, 4096, 8192) and L["block_threads"] in (64, 128, 256)
+        assert 0 <= L["waves_per_cu"] <= 32
+    # the buffers hold what one forward / backward would have produced
+    prob.forward([_to_host_bits(t) for t in src], pre)
+    o_sg = [np.zeros((r, 1024), np.uint16) for r in rows]
+    prob.backward_bf16([_to_host_bits(t) for t in grad], o_sg)
+    for j in range(32):
+        assert np.array_equal(_to_host_bits(dst[j]), pre[j])
+    for i in range(8):
+        assert np.array_equal(_to_host_bits(sg[i]), o_sg[i])
+    # and the tuned plan still computes the same thing
+    sg2 = [torch.zeros_like(t) for t in sg]
+    hp.hp_backward(plan, grad, sg2, st)
+    st.synchronize()
+    assert all(torch.equal(a, b) for a, b in zip(sg, sg2))
+    hp.hp_plan_tune(plan, src, dst, None, None, st)          # one direction only

@@ -90,7 +90,7 @@ def test_full_size_infos():
     w = wl.long_context()
     p = hp.hp_plan_create_host(w.src, w.dst, w.maps[0])
     assert p.info.row_bytes == 10240 and p.info.dst_rows_per_buf == 16384
-    assert p.info.n_tiles >= p.info.boundary_bytes // hp.hp_get_option("tile_bytes")
+    assert p.info.n_tiles >= p.info.boundary_bytes // hp.hp_get_option("tile_bytes_fwd")
     w = wl.large_scale()
     p = hp.hp_plan_create_host(w.src, w.dst, w.maps[0])
     assert (p.info.n_src_bufs, p.info.n_dst_bufs, p.info.src_copies, p.info.dst_copies) == (32, 32, 2, 8)
@@ -121,7 +121,7 @@ def test_error_codes():
     assert _code(g, wl.Grid(cp=3), ok) == binding.HP_ELAYOUT            # seq % CP
     assert _code(g, wl.Grid(cp=8, cp_split=wl.CP_ZIGZAG), replace(ok, seq=24)) == binding.HP_ELAYOUT
     assert _code(g, wl.Grid(tp=3, tp_mode=wl.TP_SEQ_SHARD), ok) == binding.HP_ELAYOUT
-    assert _code(wl.Grid(dp=200), wl.Grid(tp=8, cp=4), ok) == binding.HP_ELAYOUT   # too many buffers
+    assert _code(wl.Grid(dp=420), wl.Grid(tp=8, cp=4), ok) == binding.HP_ELAYOUT   # too many buffers
     assert _code(g, wl.Grid(tp=32), ok) == binding.HP_ELAYOUT
     bad = lambda **kw: replace(ok, **{k: np.array(v, np.int32) for k, v in kw.items()})
     assert _code(g, g, bad(img_start=[0, 14])) == binding.HP_EMAP        # runs past the end
@@ -151,6 +151,8 @@ def test_null_arguments_and_host_only_state():
     assert b"token map" in L.hp_strerror(binding.HP_EMAP)
     assert L.hp_set_option(b"no_such_key", 1) == binding.HP_EINVAL
     assert L.hp_set_option(b"block_threads_fwd", 100) == binding.HP_EINVAL
+    assert L.hp_set_option(b"tile_bytes_fwd", 3000) == binding.HP_EINVAL
+    assert L.hp_set_option(b"tile_bytes_bwd", 131072) == binding.HP_EINVAL
     assert L.hp_set_option(b"waves_per_cu_bwd", 33) == binding.HP_EINVAL
     assert hp.hp_get_option("block_threads_fwd") % 64 == 0
     assert hp.hp_get_option("nope") == -2 ** 63
@@ -158,3 +160,56 @@ def test_null_arguments_and_host_only_state():
     assert L.hp_profile_enable(0) == binding.HP_OK
     assert L.hp_profile_read(None, None, 4) == binding.HP_EINVAL
     assert L.hp_profile_read(None, None, 0) == 0
+
+
+def test_batched_plan_is_the_concatenation_of_its_microbatches():
+    """A batched plan routes microbatch m exactly like the single plan of map m,
+    with buffer indices shifted by m times the per-microbatch counts."""
+    w = wl.scaled(wl.non_colocated(n_microbatches=5), 8)
+    plan = hp.hp_plan_create_batched(w.src, w.dst, w.maps, host_only=True)
+    n_src, n_dst = w.src.n_ranks, w.dst.n_ranks
+    assert plan.info.n_maps == 5
+    assert (plan.info.n_src_bufs, plan.info.n_dst_bufs) == (5 * n_src, 5 * n_dst)
+    assert plan.info.n_rows == sum(m.n_rows for m in w.maps)
+    sb, sr = expand_segments(plan)
+    rows = plan.src_rows()
+    for mi, tm in enumerate(w.maps):
+        prob = oracle.Problem(w.src, w.dst, tm)
+        assert rows[mi * n_src:(mi + 1) * n_src] == prob.src_rows()
+        for j in range(n_dst):
+            osb, osr = prob.forward_map(j)
+            want = np.where(osb >= 0, osb + mi * n_src, -1)
+            assert np.array_equal(sb[mi * n_dst + j], want)
+            assert np.array_equal(sr[mi * n_dst + j], osr)
+    # shapes must agree across microbatches; too many buffers is refused
+    with pytest.raises(hp.HpError) as e:
+        hp.hp_plan_create_batched(w.src, w.dst, [w.maps[0], replace(w.maps[1], hidden=16)], host_only=True)
+    assert e.value.code == binding.HP_ELAYOUT
+    with pytest.raises(hp.HpError) as e:
+        hp.hp_plan_create_batched(w.src, w.dst, [w.maps[0]] * 60, host_only=True)
+    assert e.value.code == binding.HP_ELAYOUT
+    L = binding._lib()
+    out = C.c_void_p(0)
+    assert L.hp_plan_create_batched(None, None, None, 0, 1, C.byref(out)) == binding.HP_EINVAL
+
+
+def test_launch_shape_get_set_and_tile_counts():
+    w = wl.long_context()
+    p = hp.hp_plan_create_host(w.src, w.dst, w.maps[0])
+    segs = p.segments()
+    for tile in (1024, 4096, 65536):
+        p.set_launch(0, tile_bytes=tile)
+        want = sum(-(-(s.n_rows * p.info.row_bytes) // tile) for s in segs)    # dense segments: ceil by bytes
+        assert p.info.n_tiles == want
+    p.set_launch(1, tile_bytes=2048, block_threads=128, waves_per_cu=6, nontemporal=1)
+    assert p.get_launch(1) == dict(tile_bytes=2048, block_threads=128, waves_per_cu=6, nontemporal=1)
+    for bad in (dict(tile_bytes=3000), dict(block_threads=96), dict(waves_per_cu=40), dict(nontemporal=4)):
+        with pytest.raises(hp.HpError):
+            p.set_launch(0, **bad)
+    # row-strided segments are cut by whole rows
+    tm = wl.TokenMap(2, 8, 600, [0, 1], [0, 2], [8, 5])
+    q = hp.hp_plan_create_host(wl.Grid(), wl.Grid(row_order=wl.ROW_SBH), tm)
+    q.set_launch(0, tile_bytes=4096)                      # 3 rows of 1200 B per tile
+    assert q.info.n_tiles == sum(-(-s.n_rows // 3) for s in q.segments())
+    L = binding._lib()
+    assert L.hp_plan_tune(None, None, None, None, None, None) == binding.HP_EINVAL
