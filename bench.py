@@ -23,8 +23,6 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
-OPTION_KEYS = ("tile_bytes_fwd", "tile_bytes_bwd", "block_threads_fwd", "block_threads_bwd", "nontemporal_fwd", "nontemporal_bwd",
-               "waves_per_cu_fwd", "waves_per_cu_bwd")
 
 
 def log(*a):
@@ -55,6 +53,10 @@ def main() -> int:
     ap.add_argument("--workload", default="long_context",
                     choices=["tiny", "colocated4", "long_context", "non_colocated", "large_scale"])
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-tune", action="store_true",
+                    help="keep the default launch shapes instead of calling hp_plan_tune before the timed region")
+    ap.add_argument("--per-microbatch", action="store_true",
+                    help="one plan and one launch per microbatch instead of one batched plan")
     ap.add_argument("--option", action="append", default=[], metavar="KEY=INT",
                     help="library tuning knob, e.g. tile_bytes_fwd=4096 (see hp_set_option)")
     args = ap.parse_args()
@@ -82,12 +84,16 @@ def main() -> int:
     H = maps[0].hidden
     log(f"[bench] workload {w.name}: {len(maps)} microbatch(es), hidden {H}")
 
-    # ---- plans and resident buffers (one set per microbatch) ----
+    # ---- plans and resident buffers (one batched plan, or one plan per microbatch) ----
+    torch.zeros(1, device=dev)                 # HIP context up before the plan build is timed
     t0 = time.perf_counter()
-    plans = [hp.hp_plan_create(w.src, w.dst, m) for m in maps]
+    if len(maps) > 1 and not args.per_microbatch:
+        plans = [hp.hp_plan_create_batched(w.src, w.dst, maps)]
+    else:
+        plans = [hp.hp_plan_create(w.src, w.dst, m) for m in maps]
     plan_ms = (time.perf_counter() - t0) * 1e3 / len(plans)
     sets = []
-    for i, (p, m) in enumerate(zip(plans, maps)):
+    for i, p in enumerate(plans):
         rows = p.src_rows()
         src = [wl.random_bf16((r, H), w.seed * 100 + i * 7 + k, dev) for k, r in enumerate(rows)]
         dst = [wl.random_bf16((p.info.dst_rows_per_buf, H), w.seed * 100 + 50 + j, dev)
@@ -106,6 +112,16 @@ def main() -> int:
 
     stream = torch.cuda.Stream()
     n_launch = len(sets)
+
+    # ---- one-time launch-shape search on the resident buffers (not part of a step) ----
+    tune_ms = None
+    if not args.no_tune:
+        t0 = time.perf_counter()
+        for s in sets:
+            s["plan"].tune(s["src"], s["dst"], s["grad"], s["sgrad"], stream)
+        tune_ms = (time.perf_counter() - t0) * 1e3 / len(sets)
+    shapes = {"fwd": sets[0]["plan"].get_launch(0), "bwd": sets[0]["plan"].get_launch(1)}
+    log(f"[bench] launch shapes: fwd {shapes['fwd']}  bwd {shapes['bwd']}  (tune {tune_ms} ms per plan)")
 
     def step():
         for s in sets:
@@ -157,6 +173,14 @@ def main() -> int:
     del a, b
     log(f"[bench] plain copy of {2 * n_copy * 2 / 1e9:.2f} GB traffic: {copy_gbps:.0f} GB/s")
 
+    # ---- the access pattern's own ceiling: plain linear arrays, same lanes and launch search, no tables ----
+    p0i = sets[0]["plan"].info
+    arr = max(int(min(boundary, 1 << 30)) // 4096 * 4096, 1 << 20)
+    ceil_f, shape_f = hp.hp_probe_stream(1, min(p0i.dst_copies, 8), arr)
+    ceil_b, shape_b = hp.hp_probe_stream(min(p0i.dst_copies, 8), min(p0i.src_copies, 8), arr)
+    log(f"[bench] pattern ceilings: 1R:{p0i.dst_copies}W {ceil_f:.0f} GB/s {shape_f}; "
+        f"{p0i.dst_copies}R:{p0i.src_copies}W {ceil_b:.0f} GB/s {shape_b}")
+
     # ---- roofline of the dominant (slower) kernel: algorithmic bytes per launch / average launch duration ----
     dominant = "hp_backward_kernel" if b_avg >= f_avg else "hp_forward_kernel"
     dom_bytes = (bwd_bytes if dominant == "hp_backward_kernel" else fwd_bytes) / n_launch
@@ -181,10 +205,11 @@ def main() -> int:
         s, m = sets[0], maps[0]
         prob = oracle.Problem(w.src, w.dst, m)
         bits = lambda t: t.cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
-        h_src = [bits(t) for t in s["src"]]
-        h_dst = [bits(t) for t in s["dst"]]
-        h_grad = [bits(t) for t in s["grad"]]
-        h_sg = [np.zeros((r, H), np.uint16) for r in s["plan"].src_rows()]
+        n_s, n_d = w.src.n_ranks, w.dst.n_ranks            # microbatch 0 = the first buffers of the set
+        h_src = [bits(t) for t in s["src"][:n_s]]
+        h_dst = [bits(t) for t in s["dst"][:n_d]]
+        h_grad = [bits(t) for t in s["grad"][:n_d]]
+        h_sg = [np.zeros((r, H), np.uint16) for r in prob.src_rows()]
         ncores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count()
         ncores = min(ncores, int(os.environ.get("OMP_NUM_THREADS", ncores)))
         res = {}
@@ -198,7 +223,7 @@ def main() -> int:
             res[nt] = (t1 - t0, t2 - t1)
             log(f"[bench] oracle {nt} thread(s): fwd {t1 - t0:.3f} s, bwd {t2 - t1:.3f} s")
         p0 = s["plan"].info
-        ob = p0.fwd_bytes + p0.bwd_bytes
+        ob = (1 + 2 * p0.dst_copies + p0.src_copies) * m.n_rows * H * 2
         cpu_baseline = {
             "value": ob / sum(res[ncores]) / 1e9, "unit": "GB/s", "cores": ncores, "kind": "oracle",
             "sample": f"one full forward+backward pass of {w.name} (microbatch 0), {ob / 1e9:.2f} GB algorithmic",
@@ -206,7 +231,7 @@ def main() -> int:
             "one_thread_value": ob / sum(res[1]) / 1e9, "one_thread_fwd_s": res[1][0], "one_thread_bwd_s": res[1][1],
         }
         # the GPU result of the last step must equal what the oracle just computed
-        ok = all(np.array_equal(bits(t), h) for t, h in zip(s["sgrad"], h_sg))
+        ok = all(np.array_equal(bits(t), h) for t, h in zip(s["sgrad"][:n_s], h_sg))
         cpu_baseline["gpu_matches_oracle"] = bool(ok)
 
     out = {
@@ -217,15 +242,18 @@ def main() -> int:
         "config": {"workload": w.name, "src": f"tp{w.src.tp}dp{w.src.dp}",
                    "dst": f"tp{w.dst.tp}cp{w.dst.cp}dp{w.dst.dp}",
                    "batch": maps[0].batch, "seq": maps[0].seq, "hidden": H, "microbatches": len(maps),
+                   "launches_per_direction": n_launch, "launch_shapes": shapes, "tuned": not args.no_tune,
                    "image_rows": int(sum(m.n_rows for m in maps)), "boundary_bytes": boundary,
-                   **{k: hp.hp_get_option(k) for k in OPTION_KEYS}},
+                   },
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
         "forward": {"bytes": fwd_bytes, "median_ms": f_med, "min_ms": min(fwd_ms), "max_ms": max(fwd_ms),
                     "GBps": fwd_bytes / f_med / 1e6, "pct_of_hbm_peak": fwd_bytes / f_med / 1e6 / HBM_PEAK_GBPS * 100},
         "backward": {"bytes": bwd_bytes, "median_ms": b_med, "min_ms": min(bwd_ms), "max_ms": max(bwd_ms),
                      "GBps": bwd_bytes / b_med / 1e6, "pct_of_hbm_peak": bwd_bytes / b_med / 1e6 / HBM_PEAK_GBPS * 100},
-        "plan_build_ms": plan_ms,
+        "plan_build_ms": plan_ms, "plan_tune_ms": tune_ms,
         "device_copy_GBps": copy_gbps,
+        "pattern_ceiling": {"forward_GBps": ceil_f, "backward_GBps": ceil_b, "array_bytes": arr,
+                            "forward_shape": shape_f, "backward_shape": shape_b},
         "roofline": roofline,
         "cpu_baseline": cpu_baseline,
     }

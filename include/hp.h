@@ -259,6 +259,20 @@ int hp_plan_tune(hp_plan_t *plan, const void *const *src_bufs, void *const *dst_
 int hp_set_option(const char *key, int64_t value);
 int64_t hp_get_option(const char *key);     /* INT64_MIN for an unknown key */
 
+/* Streaming probe for measurement harnesses: the HBM rate of a plain kernel
+ * that reads n_read (0..8) linear arrays and writes n_write (1..8) linear arrays
+ * of bytes_per_array bytes each, with the same 16-byte lanes, one-shot
+ * workgroups and occupancy cap as the transform kernels but no segment lookup:
+ * the practical ceiling of hp_forward's 1-read : TP_dst-write pattern and of
+ * hp_backward's TP_dst-read : TP_src-write pattern on this machine.  With
+ * shape == NULL it searches the launch shapes hp_plan_tune searches and
+ * reports the best (also in *best_shape if not NULL); otherwise it times the
+ * given shape.  *gbps_out receives (n_read + n_write) * bytes / best time in
+ * GB/s.  Allocates and frees its own device buffers, stream and events;
+ * SYNCHRONOUS. */
+int hp_probe_stream(int32_t n_read, int32_t n_write, int64_t bytes_per_array,
+                    const hp_launch_t *shape, double *gbps_out, hp_launch_t *best_shape);
+
 /* Kernel timing for measurement harnesses.  hp_profile_enable(n) with n > 0
  * creates n HIP event pairs; from then on each hp_forward / hp_backward launch
  * (in call order, any thread) is stamped with the begin and end time of its own

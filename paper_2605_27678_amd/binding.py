@@ -66,7 +66,7 @@ class hp_launch_t(C.Structure):
 EXPORTS = ["hp_plan_create", "hp_plan_create_host", "hp_plan_create_batched", "hp_plan_destroy",
            "hp_plan_query", "hp_plan_src_rows", "hp_plan_segments", "hp_plan_get_launch",
            "hp_plan_set_launch", "hp_plan_tune", "hp_forward", "hp_backward",
-           "hp_set_option", "hp_get_option", "hp_profile_enable", "hp_profile_read",
+           "hp_set_option", "hp_get_option", "hp_probe_stream", "hp_profile_enable", "hp_profile_read",
            "hp_strerror", "hp_last_hip_error", "hp_version"]
 
 _handle = None
@@ -101,6 +101,9 @@ def _lib():
     L.hp_set_option.argtypes = [C.c_char_p, i64]
     L.hp_get_option.argtypes = [C.c_char_p]
     L.hp_get_option.restype = i64
+    L.hp_probe_stream.argtypes = [i32, i32, i64, C.POINTER(hp_launch_t), C.POINTER(C.c_double),
+                                  C.POINTER(hp_launch_t)]
+    L.hp_probe_stream.restype = C.c_int
     L.hp_profile_enable.argtypes = [i32]
     L.hp_profile_read.argtypes = [C.POINTER(C.c_float), C.POINTER(i32), i32]
     L.hp_strerror.argtypes = [C.c_int]
@@ -143,6 +146,16 @@ def hp_set_option(key: str, value: int) -> None:
 
 def hp_get_option(key: str) -> int:
     return int(_lib().hp_get_option(key.encode()))
+
+
+def hp_probe_stream(n_read: int, n_write: int, bytes_per_array: int, shape: Optional[dict] = None):
+    """(GB/s, launch shape) of a plain n_read : n_write streaming kernel."""
+    out = C.c_double(0.0)
+    best = hp_launch_t()
+    arg = C.byref(hp_launch_t(**shape)) if shape else None
+    _check(_lib().hp_probe_stream(n_read, n_write, int(bytes_per_array), arg, C.byref(out), C.byref(best)),
+           "hp_probe_stream")
+    return out.value, {f[0]: getattr(best, f[0]) for f in best._fields_}
 
 
 def hp_profile_enable(max_launches: int) -> None:

@@ -159,12 +159,14 @@ hp_forward_kernel(const BufTable bufs, const KParams k) {
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
 
-// binary32 -> bf16 bits, round-to-nearest-even, NaN kept quiet
-__device__ __forceinline__ uint32_t bf16_rne(float f) {
-    const uint32_t u = __float_as_uint(f);
-    const uint32_t rounded = (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
-    const uint32_t nan = (u >> 16) | 0x40u;
-    return ((u & 0x7fffffffu) > 0x7f800000u) ? nan : rounded;
+// Two binary32 values -> two bf16 in one word (lo in bits 0..15): the gfx950
+// hardware conversion (v_cvt_pk_bf16_f32), round-to-nearest-even, NaN stays NaN,
+// subnormals kept.
+__device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    const f32x2 v = {lo, hi};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
 // W = 32-bit words per lane chunk (4, 2 or 1); W == 0 means one bf16 per lane.
@@ -200,12 +202,12 @@ struct Fold {
         }
     }
     __device__ __forceinline__ V result() const {
-        if constexpr (W == 0) return (uint16_t)bf16_rne(acc[0]);
-        else if constexpr (W == 1) return bf16_rne(acc[0]) | (bf16_rne(acc[1]) << 16);
+        if constexpr (W == 0) return (uint16_t)(pack_bf16x2(acc[0], 0.f) & 0xffffu);
+        else if constexpr (W == 1) return pack_bf16x2(acc[0], acc[1]);
         else {
             V out;
 #pragma unroll
-            for (int j = 0; j < W; ++j) out[j] = bf16_rne(acc[2 * j]) | (bf16_rne(acc[2 * j + 1]) << 16);
+            for (int j = 0; j < W; ++j) out[j] = pack_bf16x2(acc[2 * j], acc[2 * j + 1]);
             return out;
         }
     }
@@ -256,6 +258,43 @@ hp_backward_kernel(const BufTable bufs, const KParams k) {
             for (int u = 0; u < kBwdUnroll; ++u) {
                 const uint32_t i = i0 + u * step;
                 if (i < n) st<V, NTS>((V *)out + i, f[u].result());
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// streaming probe: R linear arrays read, W linear arrays written, nothing else.
+// Same lane width, one-shot workgroups and occupancy cap as the kernels above,
+// but no segment lookup and no pointer table: the pattern's own ceiling.
+// ---------------------------------------------------------------------------
+struct ProbeArgs {
+    const u32x4 *rd[8];
+    u32x4 *wr[8];
+    uint32_t n_read, n_write;
+    uint64_t n_chunks;       // 16-byte chunks per array
+    uint32_t chunks_per_wg;
+};
+
+template <bool NTL, bool NTS>
+__global__ void __launch_bounds__(1024) hp_probe_kernel(const ProbeArgs a) {
+    const uint64_t base = (uint64_t)blockIdx.x * a.chunks_per_wg;
+    for (uint32_t i0 = threadIdx.x; i0 < a.chunks_per_wg; i0 += blockDim.x * kUnroll) {
+        u32x4 v[kUnroll];
+#pragma unroll
+        for (int u = 0; u < kUnroll; ++u) v[u] = (u32x4){1u, 2u, 3u, 4u};
+        for (uint32_t r = 0; r < a.n_read; ++r) {
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const uint64_t i = base + i0 + (uint64_t)u * blockDim.x;
+                if (i0 + u * blockDim.x < a.chunks_per_wg && i < a.n_chunks) v[u] ^= ld<u32x4, NTL>(a.rd[r] + i);
+            }
+        }
+        for (uint32_t w = 0; w < a.n_write; ++w) {
+#pragma unroll
+            for (int u = 0; u < kUnroll; ++u) {
+                const uint64_t i = base + i0 + (uint64_t)u * blockDim.x;
+                if (i0 + u * blockDim.x < a.chunks_per_wg && i < a.n_chunks) st<u32x4, NTS>(a.wr[w] + i, v[u]);
             }
         }
     }
@@ -502,33 +541,39 @@ const OptionDesc kOptions[] = {
     {"waves_per_cu_bwd", &hp::Options::waves_per_cu_bwd, 0, 32, 1, false},
 };
 
-// Times `reps` launches of one candidate and returns the best kernel duration
-// in milliseconds, or a negative error.
+// Times `reps` launches of one candidate (after one warm-up launch).  Returns
+// the minimum or the median kernel duration in milliseconds, or a negative
+// value on a HIP error.
 float time_candidate(const hp_plan *p, Direction dir, const hp::Launch &L, const BufTable &bt, int width,
-                     hipStream_t stream, EventPair ev, int reps) {
-    float best = 1e30f;
-    for (int r = 0; r < reps + 1; ++r) {                    // first launch is a warm-up
+                     hipStream_t stream, EventPair ev, int reps, bool median) {
+    float t[16];
+    if (reps > 16) reps = 16;
+    for (int r = -1; r < reps; ++r) {
         if (enqueue(p, dir, L, bt, width, stream, ev) != HP_OK) return -1.f;
         if (hip_failed(hipEventSynchronize(ev.stop))) return -1.f;
         float ms = 0.f;
         if (hip_failed(hipEventElapsedTime(&ms, ev.start, ev.stop))) return -1.f;
-        if (r > 0) best = std::min(best, ms);
+        if (r >= 0) t[r] = ms;
     }
-    return best;
+    std::sort(t, t + reps);
+    return median ? t[reps / 2] : t[0];
 }
 
 // Searches the launch shapes that matter for a streaming kernel on this chip:
 // tile size x workgroup size (1, 2 or 4 sixteen-byte chunks per lane) x the
-// resident-wave cap.  Keeps the plan's cache policy.
+// resident-wave cap, keeping the plan's cache policy.  A coarse pass ranks all
+// shapes on two launches each; the best few and the current shape are then
+// re-timed by the median of seven launches, because the top of the ranking is
+// flat and single timings are noisy.
 int tune_direction(hp_plan *p, Direction dir, const BufTable &bt, int width, hipStream_t stream) {
     hipEvent_t e0 = nullptr, e1 = nullptr;
     if (hip_failed(hipEventCreate(&e0))) return HP_EHIP;
     if (hip_failed(hipEventCreate(&e1))) { (void)hipEventDestroy(e0); return HP_EHIP; }
     const EventPair ev{e0, e1};
     hp::Launch &cur = dir == kForward ? p->fwd : p->bwd;
-    hp::Launch best = cur;
-    float best_ms = time_candidate(p, dir, cur, bt, width, stream, ev, 3);
-    int rc = best_ms < 0 ? HP_EHIP : HP_OK;
+    struct Cand { float ms; hp::Launch L; };
+    std::vector<Cand> cands;
+    int rc = HP_OK;
     const int blocks[] = {64, 128, 256};
     const int caps[] = {4, 6, 8, 12, 16, 24, 0};
     for (int v = 0; v <= 3 && rc == HP_OK; ++v) {                       // 1, 2, 4, 8 KiB tiles
@@ -537,23 +582,55 @@ int tune_direction(hp_plan *p, Direction dir, const BufTable &bt, int width, hip
             if (chunks != 1 && chunks != 2 && chunks != 4) continue;
             for (int cap : caps) {
                 if (cap && cap < 2 * (b / 64)) continue;                // cap below two workgroups
-                hp::Launch L{v, b, cap, cur.nontemporal};
-                const float ms = time_candidate(p, dir, L, bt, width, stream, ev, 2);
+                const hp::Launch L{v, b, cap, cur.nontemporal};
+                const float ms = time_candidate(p, dir, L, bt, width, stream, ev, 2, false);
                 if (ms < 0) { rc = HP_EHIP; break; }
-                if (ms < best_ms) { best_ms = ms; best = L; }
+                cands.push_back(Cand{ms, L});
             }
             if (rc != HP_OK) break;
         }
     }
     if (rc == HP_OK) {
-        // confirm the winner against the runner-up noise: re-time it with more repetitions
-        const float again = time_candidate(p, dir, best, bt, width, stream, ev, 5);
-        if (again < 0) rc = HP_EHIP;
-        else cur = best;
+        std::sort(cands.begin(), cands.end(), [](const Cand &x, const Cand &y) { return x.ms < y.ms; });
+        if (cands.size() > 5) cands.resize(5);
+        cands.push_back(Cand{0.f, cur});
+        hp::Launch best = cur;
+        float best_ms = 1e30f;
+        for (const Cand &c : cands) {
+            const float ms = time_candidate(p, dir, c.L, bt, width, stream, ev, 7, true);
+            if (ms < 0) { rc = HP_EHIP; break; }
+            if (ms < best_ms) { best_ms = ms; best = c.L; }
+        }
+        if (rc == HP_OK) cur = best;
     }
     (void)hipEventDestroy(e0);
     (void)hipEventDestroy(e1);
     return rc;
+}
+
+float time_probe(const ProbeArgs &a, const hp::Launch &L, hipStream_t stream, EventPair ev, int reps) {
+    ProbeArgs args = a;
+    args.chunks_per_wg = hp::tile_bytes_of(L.tile_variant) / 16u;
+    LaunchCfg c;
+    c.grid = dim3((unsigned)((a.n_chunks + args.chunks_per_wg - 1) / args.chunks_per_wg));
+    c.block = dim3((unsigned)L.block);
+    c.lds_bytes = lds_for_cap(L.block, L.waves_per_cu);
+    c.stream = stream;
+    c.ev = ev;
+    float best = 1e30f;
+    for (int r = 0; r < reps + 1; ++r) {
+        switch (L.nontemporal & 3) {
+            case 0: HP_LAUNCH((hp_probe_kernel<false, false>), c, args); break;
+            case 1: HP_LAUNCH((hp_probe_kernel<true, false>), c, args); break;
+            case 2: HP_LAUNCH((hp_probe_kernel<false, true>), c, args); break;
+            default: HP_LAUNCH((hp_probe_kernel<true, true>), c, args); break;
+        }
+        if (hip_failed(hipGetLastError()) || hip_failed(hipEventSynchronize(ev.stop))) return -1.f;
+        float ms = 0.f;
+        if (hip_failed(hipEventElapsedTime(&ms, ev.start, ev.stop))) return -1.f;
+        if (r > 0) best = std::min(best, ms);
+    }
+    return best;
 }
 
 }  // namespace
@@ -669,6 +746,77 @@ int hp_plan_tune(hp_plan_t *p, const void *const *src_bufs, void *const *dst_buf
         if (rc == HP_OK) rc = tune_direction(p, kBackward, bt, width, (hipStream_t)stream);
     }
     return rc;
+}
+
+int hp_probe_stream(int32_t n_read, int32_t n_write, int64_t bytes_per_array, const hp_launch_t *shape,
+                    double *gbps_out, hp_launch_t *best_shape) {
+    if (n_read < 0 || n_read > 8 || n_write < 1 || n_write > 8 || !gbps_out) return HP_EINVAL;
+    if (bytes_per_array < 65536 || bytes_per_array % 16 || bytes_per_array > ((int64_t)1 << 36)) return HP_EINVAL;
+    hp::Launch fixed{};
+    if (shape) {
+        fixed = hp::Launch{hp::tile_variant_of(shape->tile_bytes), shape->block_threads, shape->waves_per_cu,
+                           shape->nontemporal};
+        if (!launch_ok(fixed)) return HP_EINVAL;
+    }
+    ProbeArgs a;
+    std::memset(&a, 0, sizeof(a));
+    a.n_read = (uint32_t)n_read;
+    a.n_write = (uint32_t)n_write;
+    a.n_chunks = (uint64_t)bytes_per_array / 16u;
+    void *mem[16] = {nullptr};
+    hipEvent_t e0 = nullptr, e1 = nullptr;
+    hipStream_t stream = nullptr;
+    int rc = HP_OK;
+    for (int i = 0; i < n_read + n_write && rc == HP_OK; ++i) {
+        hipError_t e = hipMalloc(&mem[i], (size_t)bytes_per_array);
+        if (e == hipErrorOutOfMemory) { g_last_hip_error = (int)e; rc = HP_ENOMEM; }
+        else if (hip_failed(e)) rc = HP_EHIP;
+        else if (hip_failed(hipMemset(mem[i], i + 1, (size_t)bytes_per_array))) rc = HP_EHIP;
+    }
+    for (int i = 0; i < n_read; ++i) a.rd[i] = (const u32x4 *)mem[i];
+    for (int i = 0; i < n_write; ++i) a.wr[i] = (u32x4 *)mem[n_read + i];
+    if (rc == HP_OK && (hip_failed(hipEventCreate(&e0)) || hip_failed(hipEventCreate(&e1)) ||
+                        hip_failed(hipStreamCreate(&stream))))
+        rc = HP_EHIP;
+    float best_ms = 1e30f;
+    hp::Launch best = fixed;
+    if (rc == HP_OK) {
+        const EventPair ev{e0, e1};
+        if (shape) {
+            best_ms = time_probe(a, fixed, stream, ev, 5);
+            if (best_ms < 0) rc = HP_EHIP;
+        } else {
+            const int blocks[] = {64, 128, 256};
+            const int caps[] = {4, 6, 8, 12, 16, 24, 0};
+            const int nt = (n_read > n_write) ? 3 : 2;
+            for (int v = 0; v <= 3 && rc == HP_OK; ++v)
+                for (int b : blocks) {
+                    const int chunks = (int)(hp::tile_bytes_of(v) / 16u) / b;
+                    if (chunks != 1 && chunks != 2 && chunks != 4) continue;
+                    for (int cap : caps) {
+                        if (cap && cap < 2 * (b / 64)) continue;
+                        const hp::Launch L{v, b, cap, nt};
+                        const float ms = time_probe(a, L, stream, ev, 3);
+                        if (ms < 0) { rc = HP_EHIP; break; }
+                        if (ms < best_ms) { best_ms = ms; best = L; }
+                    }
+                    if (rc != HP_OK) break;
+                }
+        }
+    }
+    if (stream) { (void)hipStreamSynchronize(stream); (void)hipStreamDestroy(stream); }
+    if (e0) (void)hipEventDestroy(e0);
+    if (e1) (void)hipEventDestroy(e1);
+    for (void *m : mem) if (m) (void)hipFree(m);
+    if (rc != HP_OK) return rc;
+    *gbps_out = (double)(n_read + n_write) * (double)bytes_per_array / ((double)best_ms * 1e-3) / 1e9;
+    if (best_shape) {
+        best_shape->tile_bytes = (int32_t)hp::tile_bytes_of(best.tile_variant);
+        best_shape->block_threads = best.block;
+        best_shape->waves_per_cu = best.waves_per_cu;
+        best_shape->nontemporal = best.nontemporal;
+    }
+    return HP_OK;
 }
 
 int hp_set_option(const char *key, int64_t value) {

@@ -38,8 +38,9 @@ struct Launch {
 };
 
 struct Options {
-    int64_t tile_bytes_fwd = 4096, tile_bytes_bwd = 4096;
-    int64_t block_threads_fwd = 256, block_threads_bwd = 256;
+    // defaults = what hp_plan_tune picks most often on the long-context workload
+    int64_t tile_bytes_fwd = 2048, tile_bytes_bwd = 1024;
+    int64_t block_threads_fwd = 128, block_threads_bwd = 64;
     int64_t waves_per_cu_fwd = 16, waves_per_cu_bwd = 16;   // 0 = no cap
     int64_t nontemporal_fwd = 2, nontemporal_bwd = 3;       // bit 0 loads, bit 1 stores
 };

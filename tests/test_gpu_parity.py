@@ -329,3 +329,13 @@ def test_tune_keeps_results_exact_and_picks_a_valid_shape():
     st.synchronize()
     assert all(torch.equal(a, b) for a, b in zip(sg, sg2))
     hp.hp_plan_tune(plan, src, dst, None, None, st)          # one direction only
+
+
+def test_stream_probe_reports_a_rate():
+    gbps, shape = hp.hp_probe_stream(1, 4, 8 << 20)
+    assert gbps > 50.0 and shape["tile_bytes"] in (1024, 2048, 4096, 8192)
+    fixed = dict(tile_bytes=4096, block_threads=256, waves_per_cu=16, nontemporal=2)
+    gbps2, shape2 = hp.hp_probe_stream(4, 1, 8 << 20, fixed)
+    assert gbps2 > 50.0 and shape2 == fixed
+    with pytest.raises(hp.HpError):
+        hp.hp_probe_stream(9, 1, 8 << 20)
