@@ -90,13 +90,13 @@ __device__ __forceinline__ TileView locate_tile(const KParams &k, uint32_t tile)
     v.dst_buf0 = s.dst_buf0;
     if (s.pitch_rows == 1) {
         const uint64_t off = (uint64_t)t * k.tile_bytes;
-        const uint64_t left = s.nbytes - off;
+        const uint64_t left = (uint64_t)s.n_rows * k.row_bytes - off;
         v.src_off = s.src_off + off;
         v.dst_off = s.dst_off + off;
         v.nbytes = left < k.tile_bytes ? (uint32_t)left : k.tile_bytes;
     } else {
         const uint64_t row0 = (uint64_t)t * k.rows_per_tile;
-        const uint64_t rows_left = s.nbytes / k.row_bytes - row0;
+        const uint64_t rows_left = s.n_rows - row0;
         const uint32_t rows = rows_left < k.rows_per_tile ? (uint32_t)rows_left : k.rows_per_tile;
         v.src_off = s.src_off + row0 * k.row_bytes;
         v.dst_off = s.dst_off + row0 * s.pitch_rows * k.row_bytes;
@@ -105,38 +105,55 @@ __device__ __forceinline__ TileView locate_tile(const KParams &k, uint32_t tile)
     return v;
 }
 
-constexpr int kUnroll = 4;
 
 // ---------------------------------------------------------------------------
 // forward: tile of the source buffer -> the same bytes in NREP destination copies
 // ---------------------------------------------------------------------------
+// U chunks per lane starting at chunk `done`, as straight-line code: all loads
+// are issued before the first store.  With GUARD the group is the ragged end of
+// a tile: lanes past the end re-read the tile's last chunk and skip the stores,
+// so there is still no branch around a load.
+template <typename V, int NREP, int U, bool GUARD, bool NTL, bool NTS>
+__device__ __forceinline__ void forward_group(const BufTable &bufs, const KParams &k, const TileView &t,
+                                              const char *src, uint32_t nrep, uint32_t done, uint32_t n) {
+    V v[U];
+    uint32_t i[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        i[u] = done + u * blockDim.x + threadIdx.x;
+        v[u] = ld<V, NTL>((const V *)src + (GUARD ? min(i[u], n - 1) : i[u]));
+    }
+#pragma unroll 4
+    for (uint32_t r = 0; r < nrep; ++r) {
+        char *dst = (char *)bufs.p[k.dst_base + t.dst_buf0 + r] + t.dst_off;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (!GUARD || i[u] < n) st<V, NTS>((V *)dst + i[u], v[u]);
+    }
+}
+
 template <typename V, int NREP, bool NTL, bool NTS>
 __global__ void __launch_bounds__(1024)
 hp_forward_kernel(const BufTable bufs, const KParams k) {
     const TileView t = locate_tile(k, blockIdx.x);
     const uint32_t nrep = NREP > 0 ? (uint32_t)NREP : k.dst_copies;
     const char *src = (const char *)bufs.p[t.src_buf] + t.src_off;
-    const uint32_t n = t.nbytes / (uint32_t)sizeof(V);
+    const uint32_t n = t.nbytes / (uint32_t)sizeof(V);      // lane chunks in this tile, >= 1
     const uint32_t step = blockDim.x;
 
     if (t.pitch_rows == 1) {
-        for (uint32_t i0 = threadIdx.x; i0 < n; i0 += step * kUnroll) {
-            V v[kUnroll];
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                const uint32_t i = i0 + u * step;
-                if (i < n) v[u] = ld<V, NTL>((const V *)src + i);
-            }
-#pragma unroll 4
-            for (uint32_t r = 0; r < nrep; ++r) {
-                char *dst = (char *)bufs.p[k.dst_base + t.dst_buf0 + r] + t.dst_off;
-#pragma unroll
-                for (int u = 0; u < kUnroll; ++u) {
-                    const uint32_t i = i0 + u * step;
-                    if (i < n) st<V, NTS>((V *)dst + i, v[u]);
-                }
-            }
+        uint32_t done = 0;                                   // uniform
+        for (; n - done >= 4 * step; done += 4 * step)
+            forward_group<V, NREP, 4, false, NTL, NTS>(bufs, k, t, src, nrep, done, n);
+        if (n - done >= 2 * step) {
+            forward_group<V, NREP, 2, false, NTL, NTS>(bufs, k, t, src, nrep, done, n);
+            done += 2 * step;
         }
+        if (n - done >= step) {
+            forward_group<V, NREP, 1, false, NTL, NTS>(bufs, k, t, src, nrep, done, n);
+            done += step;
+        }
+        if (n - done > 0) forward_group<V, NREP, 1, true, NTL, NTS>(bufs, k, t, src, nrep, done, n);
     } else {
         // row-strided destination ([S,B,H] order with several samples per rank)
         const uint64_t pitch = (uint64_t)t.pitch_rows * k.row_bytes;
@@ -213,7 +230,60 @@ struct Fold {
     }
 };
 
-constexpr int kBwdUnroll = 2;
+// U chunks per lane starting at chunk `done`, straight-line: the loads of all
+// replicas (groups of four when the replica count is only known at run time) are
+// issued before the first add.  GUARD as in forward_group.
+template <int W, int NREP, int U, bool GUARD, bool NTL, bool NTS>
+__device__ __forceinline__ void backward_group(const BufTable &bufs, const KParams &k, const TileView &t,
+                                               uint32_t nrep, uint32_t done, uint32_t n) {
+    typedef typename Chunk<W>::type V;
+    constexpr int G = NREP > 0 ? NREP : 4;
+    const bool dense = t.pitch_rows == 1;
+    const uint64_t pitch = (uint64_t)t.pitch_rows * k.row_bytes;
+    uint32_t i[U];
+    uint64_t goff[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        i[u] = done + u * blockDim.x + threadIdx.x;
+        const uint32_t byte = (GUARD ? min(i[u], n - 1) : i[u]) * (uint32_t)sizeof(V);
+        if (dense) goff[u] = byte;
+        else {
+            const uint32_t row = byte / k.row_bytes;
+            goff[u] = row * pitch + (byte - row * k.row_bytes);
+        }
+    }
+    Fold<W> f[U];
+    for (uint32_t r0 = 0; r0 < nrep; r0 += G) {
+        V v[G][U];
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            // past the last replica of a run-time count: re-read the last one, result unused
+            const uint32_t r = NREP > 0 ? r0 + g : min(r0 + g, nrep - 1);
+            const char *gp = (const char *)bufs.p[k.dst_base + t.dst_buf0 + r] + t.dst_off;
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[g][u] = ld<V, NTL>((const V *)(gp + goff[u]));
+        }
+        // ascending tp: copy 0 starts the accumulator, copies 1.. are added in order
+#pragma unroll
+        for (int g = 0; g < G; ++g) {
+            if (NREP > 0 || r0 + g < nrep) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) {
+                    if (g == 0 && r0 == 0) f[u].first(v[g][u]); else f[u].add(v[g][u]);
+                }
+            }
+        }
+    }
+    V res[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) res[u] = f[u].result();
+    for (uint32_t s = 0; s < k.src_copies; ++s) {
+        char *out = (char *)bufs.p[t.src_buf + s] + t.src_off;
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (!GUARD || i[u] < n) st<V, NTS>((V *)out + i[u], res[u]);
+    }
+}
 
 template <int W, int NREP, bool NTL, bool NTS>
 __global__ void __launch_bounds__(1024)
@@ -221,46 +291,16 @@ hp_backward_kernel(const BufTable bufs, const KParams k) {
     typedef typename Chunk<W>::type V;
     const TileView t = locate_tile(k, blockIdx.x);
     const uint32_t nrep = NREP > 0 ? (uint32_t)NREP : k.dst_copies;
-    const uint32_t n = t.nbytes / (uint32_t)sizeof(V);
+    const uint32_t n = t.nbytes / (uint32_t)sizeof(V);      // lane chunks in this tile, >= 1
     const uint32_t step = blockDim.x;
-    const uint64_t pitch = (uint64_t)t.pitch_rows * k.row_bytes;
-    const bool dense = t.pitch_rows == 1;
-
-    for (uint32_t i0 = threadIdx.x; i0 < n; i0 += step * kBwdUnroll) {
-        Fold<W> f[kBwdUnroll];
-        uint64_t goff[kBwdUnroll];
-#pragma unroll
-        for (int u = 0; u < kBwdUnroll; ++u) {
-            const uint32_t i = i0 + u * step;
-            const uint32_t byte = i * (uint32_t)sizeof(V);
-            if (dense) goff[u] = byte;
-            else {
-                const uint32_t row = byte / k.row_bytes;
-                goff[u] = row * pitch + (byte - row * k.row_bytes);
-            }
-        }
-        // ascending tp: copy 0 starts the accumulator, copies 1.. are added in order
-#pragma unroll 4
-        for (uint32_t r = 0; r < nrep; ++r) {
-            const char *g = (const char *)bufs.p[k.dst_base + t.dst_buf0 + r] + t.dst_off;
-#pragma unroll
-            for (int u = 0; u < kBwdUnroll; ++u) {
-                const uint32_t i = i0 + u * step;
-                if (i < n) {
-                    const V v = ld<V, NTL>((const V *)(g + goff[u]));
-                    if (r == 0) f[u].first(v); else f[u].add(v);
-                }
-            }
-        }
-        for (uint32_t s = 0; s < k.src_copies; ++s) {
-            char *out = (char *)bufs.p[t.src_buf + s] + t.src_off;
-#pragma unroll
-            for (int u = 0; u < kBwdUnroll; ++u) {
-                const uint32_t i = i0 + u * step;
-                if (i < n) st<V, NTS>((V *)out + i, f[u].result());
-            }
-        }
+    uint32_t done = 0;                                       // uniform
+    for (; n - done >= 2 * step; done += 2 * step)
+        backward_group<W, NREP, 2, false, NTL, NTS>(bufs, k, t, nrep, done, n);
+    if (n - done >= step) {
+        backward_group<W, NREP, 1, false, NTL, NTS>(bufs, k, t, nrep, done, n);
+        done += step;
     }
+    if (n - done > 0) backward_group<W, NREP, 1, true, NTL, NTS>(bufs, k, t, nrep, done, n);
 }
 
 // ---------------------------------------------------------------------------
@@ -276,28 +316,47 @@ struct ProbeArgs {
     uint32_t chunks_per_wg;
 };
 
+template <int U, bool GUARD, bool NTL, bool NTS>
+__device__ __forceinline__ void probe_group(const ProbeArgs &a, uint64_t base, uint32_t done, uint32_t n) {
+    uint32_t i[U];
+    u32x4 acc[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        i[u] = done + u * blockDim.x + threadIdx.x;
+        acc[u] = (u32x4){1u, 2u, 3u, 4u};
+    }
+    for (uint32_t r0 = 0; r0 < a.n_read; r0 += 4) {
+        u32x4 v[4][U];
+#pragma unroll
+        for (int g = 0; g < 4; ++g) {
+            const u32x4 *p = a.rd[min(r0 + g, a.n_read - 1)] + base;
+#pragma unroll
+            for (int u = 0; u < U; ++u) v[g][u] = ld<u32x4, NTL>(p + (GUARD ? min(i[u], n - 1) : i[u]));
+        }
+#pragma unroll
+        for (int g = 0; g < 4; ++g)
+            if (r0 + g < a.n_read) {
+#pragma unroll
+                for (int u = 0; u < U; ++u) acc[u] ^= v[g][u];
+            }
+    }
+    for (uint32_t w = 0; w < a.n_write; ++w) {
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if (!GUARD || i[u] < n) st<u32x4, NTS>(a.wr[w] + base + i[u], acc[u]);
+    }
+}
+
 template <bool NTL, bool NTS>
 __global__ void __launch_bounds__(1024) hp_probe_kernel(const ProbeArgs a) {
     const uint64_t base = (uint64_t)blockIdx.x * a.chunks_per_wg;
-    for (uint32_t i0 = threadIdx.x; i0 < a.chunks_per_wg; i0 += blockDim.x * kUnroll) {
-        u32x4 v[kUnroll];
-#pragma unroll
-        for (int u = 0; u < kUnroll; ++u) v[u] = (u32x4){1u, 2u, 3u, 4u};
-        for (uint32_t r = 0; r < a.n_read; ++r) {
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                const uint64_t i = base + i0 + (uint64_t)u * blockDim.x;
-                if (i0 + u * blockDim.x < a.chunks_per_wg && i < a.n_chunks) v[u] ^= ld<u32x4, NTL>(a.rd[r] + i);
-            }
-        }
-        for (uint32_t w = 0; w < a.n_write; ++w) {
-#pragma unroll
-            for (int u = 0; u < kUnroll; ++u) {
-                const uint64_t i = base + i0 + (uint64_t)u * blockDim.x;
-                if (i0 + u * blockDim.x < a.chunks_per_wg && i < a.n_chunks) st<u32x4, NTS>(a.wr[w] + i, v[u]);
-            }
-        }
-    }
+    const uint64_t left = a.n_chunks - base;
+    const uint32_t n = left < a.chunks_per_wg ? (uint32_t)left : a.chunks_per_wg;
+    const uint32_t step = blockDim.x;
+    uint32_t done = 0;
+    for (; n - done >= 2 * step; done += 2 * step) probe_group<2, false, NTL, NTS>(a, base, done, n);
+    if (n - done >= step) { probe_group<1, false, NTL, NTS>(a, base, done, n); done += step; }
+    if (n - done > 0) probe_group<1, true, NTL, NTS>(a, base, done, n);
 }
 
 // ---------------------------------------------------------------------------

@@ -150,7 +150,8 @@ int make_tables(hp_plan *p) {
         Seg &d = p->dsegs[i];
         d.src_off = (uint64_t)s.src_row0 * p->row_bytes;
         d.dst_off = (uint64_t)s.dst_row0 * p->row_bytes;
-        d.nbytes = (uint64_t)s.n_rows * p->row_bytes;
+        d.n_rows = (uint32_t)s.n_rows;
+        d.reserved = 0;
         d.pitch_rows = (uint32_t)s.dst_row_stride;
         d.src_buf = (uint16_t)s.src_buf;
         d.dst_buf0 = (uint16_t)s.dst_buf0;

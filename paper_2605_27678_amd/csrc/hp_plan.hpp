@@ -14,10 +14,11 @@ namespace hp {
 struct alignas(16) Seg {
     uint64_t src_off;     // bytes from the base of the source buffer
     uint64_t dst_off;     // bytes from the base of each destination copy
-    uint64_t nbytes;      // rows * row_bytes
+    uint32_t n_rows;      // rows of row_bytes each
     uint32_t pitch_rows;  // destination row pitch in rows (1 = dense)
     uint16_t src_buf;     // source buffer index of copy tp = 0
     uint16_t dst_buf0;    // first destination buffer index
+    uint32_t reserved;
 };
 static_assert(sizeof(Seg) == 32, "segment descriptor must stay 32 bytes");
 
