@@ -84,8 +84,10 @@ extern "C" {
 /* hp_layout_t.row_order (destination only) */
 #define HP_ROW_BSH 0
 #define HP_ROW_SBH 1
-/* hp_token_map_t.dtype */
+/* hp_token_map_t.dtype: element type of the activations and gradients */
 #define HP_BF16 0
+#define HP_F32  1   /* the paper validates in FP32 as well as BF16; forward moves
+                       4-byte elements, backward folds them with no final rounding */
 
 #define HP_MAX_BUFFERS 448   /* source + destination buffers of one plan, all microbatches   */
 #define HP_MAX_TP      16    /* replicas summed by hp_backward                               */
@@ -112,7 +114,7 @@ typedef struct hp_layout {
  * source dp ranks. */
 typedef struct hp_token_map {
     int32_t batch, seq, hidden;
-    int32_t dtype;                 /* HP_BF16 */
+    int32_t dtype;                 /* HP_BF16 or HP_F32 */
     int32_t n_images;
     const int32_t *img_sample;
     const int32_t *img_start;
@@ -207,8 +209,9 @@ int hp_plan_segments(const hp_plan_t *plan, hp_segment_t *out, int32_t cap);
  *             Exactly the image-token rows are written; all other bytes (the
  *             text embeddings the caller placed there) are left as found.
  *   stream:   a hipStream_t (NULL = the default stream).
- * Pointers must be aligned to 2 bytes; 16-byte alignment selects the vector
- * path.  Returns after enqueueing. */
+ * Pointers must be aligned to the element size; 16-byte alignment (with a row
+ * size that is a multiple of 16) selects the vector path.  Returns after
+ * enqueueing. */
 int hp_forward(const hp_plan_t *plan, const void *const *src_bufs,
                void *const *dst_bufs, void *stream);
 
@@ -226,6 +229,21 @@ int hp_forward(const hp_plan_t *plan, const void *const *src_bufs,
  */
 int hp_backward(const hp_plan_t *plan, const void *const *dst_grad_bufs,
                 void *const *src_grad_bufs, void *stream);
+
+/* hp_backward_accumulate - as hp_backward, but the source side holds binary32
+ * gradient ACCUMULATORS that are added to instead of overwritten: the gradients
+ * that accumulate on the packed boundary tensor over the microbatches of a
+ * pipeline window before the encoder backward consumes them (appendix "Pipeline
+ * schedule details", phase 3).  For every image-token row the replicas are
+ * folded as in hp_backward (ascending tp, binary32, no rounding to the gradient
+ * dtype) and the sum s is applied as acc = acc + s to every source TP copy.
+ *   dst_grad_bufs:  as for hp_backward (bf16 or f32 per the plan's dtype).
+ *   src_accum_bufs: HOST array of n_src_bufs DEVICE pointers to binary32 arrays
+ *                   [rows_i, hidden], read and written; 4-byte aligned (16-byte
+ *                   alignment and hidden % 4 == 0 select the vector path).
+ * Uses the plan's hp_backward launch shape. */
+int hp_backward_accumulate(const hp_plan_t *plan, const void *const *dst_grad_bufs,
+                           void *const *src_accum_bufs, void *stream);
 
 /* Launch shape of one direction of a plan (direction 0 = hp_forward,
  * 1 = hp_backward).  A plan starts from the process-wide defaults below. */
@@ -279,7 +297,7 @@ int hp_probe_stream(int32_t n_read, int32_t n_write, int64_t bytes_per_array,
  * kernel dispatch until the n pairs are used up; later launches are not timed.
  * n = 0 disables timing and frees the events.  hp_profile_read waits for the
  * recorded launches, writes their kernel durations in milliseconds to ms[] and
- * their kind (0 = hp_forward, 1 = hp_backward) to kinds[] (host arrays of `cap`
+ * their kind (0 = hp_forward, 1 = hp_backward, 2 = hp_backward_accumulate) to kinds[] (host arrays of `cap`
  * entries), rewinds the recorder and returns the number of launches recorded. */
 int hp_profile_enable(int32_t max_launches);
 int hp_profile_read(float *ms, int32_t *kinds, int32_t cap);

@@ -251,6 +251,60 @@ int orc_forward(const orc_grid_t *src, const orc_grid_t *dst, const orc_map_t *m
     return 0;
 }
 
+/* Backward for either gradient dtype (0 = bf16, 1 = binary32), overwriting or
+ * accumulating.  Same walk and same ascending-tp binary32 left fold as
+ * orc_backward_bf16 below.  Overwrite: the sum is rounded to the gradient dtype
+ * (no rounding for binary32) and stored to every source TP copy.  Accumulate:
+ * every source TP copy is a binary32 accumulator and receives acc = acc + sum,
+ * one more binary32 add - the gradients that pile up on the packed boundary
+ * tensor over the microbatches of a pipeline window ("Pipeline schedule
+ * details", phase 3: accumulated gradients are handed to the backward
+ * transform). */
+int orc_backward(const orc_grid_t *src, const orc_grid_t *dst, const orc_map_t *m,
+                 int32_t dtype, int32_t accumulate,
+                 const void *const *dst_grads, void *const *src_out)
+{
+    if (check_shapes(src, dst, m)) return -1;
+    if (dtype != 0 && dtype != 1) return -1;
+    const int64_t H = m->hidden;
+    const int32_t n_dst = dst->tp * dst->cp * dst->dp;
+    const int64_t rows = orc_dst_rows(dst, m);
+    const int32_t n_rep = dst->tp_mode == 1 ? 1 : dst->tp;
+    const int32_t n_slices = n_dst / n_rep;
+    const int64_t total = (int64_t)n_slices * rows;
+#pragma omp parallel for schedule(static)
+    for (int64_t i = 0; i < total; ++i) {
+        int32_t buf0 = (int32_t)(i / rows) * n_rep;
+        int64_t r = i % rows;
+        int32_t b, k, j, d; int64_t s, srow;
+        dst_global(dst, m, buf0, r, &b, &s);
+        if (!find_image(m, b, s, &k, &j)) continue;
+        src_locate(src, m, k, j, &d, &srow);
+        for (int64_t h = 0; h < H; ++h) {
+            volatile float acc = 0.0f;
+            for (int32_t t = 0; t < n_rep; ++t) {
+                float g = dtype == 0 ? bf16_to_f32(((const uint16_t *)dst_grads[buf0 + t])[r * H + h])
+                                     : ((const float *)dst_grads[buf0 + t])[r * H + h];
+                if (t == 0) acc = g;          /* the fold starts AT copy 0, not at +0.0 */
+                else acc = acc + g;
+            }
+            for (int32_t ts = 0; ts < src->tp; ++ts) {
+                void *out = src_out[d * src->tp + ts];
+                if (accumulate) {
+                    volatile float a = ((float *)out)[srow * H + h];
+                    a = a + acc;
+                    ((float *)out)[srow * H + h] = a;
+                } else if (dtype == 0) {
+                    ((uint16_t *)out)[srow * H + h] = f32_to_bf16(acc);
+                } else {
+                    ((float *)out)[srow * H + h] = acc;
+                }
+            }
+        }
+    }
+    return 0;
+}
+
 /* Backward (bf16 in, binary32 accumulate, bf16 out).  For every image-token row
  * of every (dp, cp[, tp piece]) destination slice: fold the TP replicas of the
  * gradient in ascending tp order, round once, and store the result into every

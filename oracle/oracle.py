@@ -145,6 +145,30 @@ class Problem:
         if rc:
             raise ValueError("oracle: layout does not divide the token map")
 
+    def _backward(self, dtype: int, accumulate: bool, dst_grads, src_out) -> None:
+        assert len(dst_grads) == self.n_dst and len(src_out) == self.n_src
+        in_dt = np.uint16 if dtype == 0 else np.float32
+        out_dt = np.float32 if (accumulate or dtype == 1) else np.uint16
+        for a in dst_grads:
+            assert a.dtype == in_dt and a.size == self.dst_rows() * self.hidden
+        for a, r in zip(src_out, self.src_rows()):
+            assert a.dtype == out_dt and a.size == r * self.hidden
+        rc = lib().orc_backward(C.byref(self.src), C.byref(self.dst), C.byref(self.map),
+                                C.c_int32(dtype), C.c_int32(1 if accumulate else 0),
+                                self._ptrs(dst_grads), self._ptrs(src_out))
+        if rc:
+            raise ValueError("oracle: layout does not divide the token map")
+
+    def backward_f32(self, dst_grads, src_grads) -> None:
+        """binary32 gradients in, binary32 out (in place on src_grads)."""
+        self._backward(1, False, dst_grads, src_grads)
+
+    def backward_accumulate(self, dst_grads, src_accum) -> None:
+        """bf16 (uint16 bits) or binary32 gradients in; the float32 arrays in
+        src_accum are added to in place."""
+        self._backward(0 if dst_grads[0].dtype == np.uint16 else 1, True, dst_grads, src_accum)
+
+
 
 def f32_to_bf16(x: float) -> int:
     return int(lib().orc_f32_to_bf16(C.c_float(x)))

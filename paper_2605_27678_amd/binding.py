@@ -65,7 +65,7 @@ class hp_launch_t(C.Structure):
 
 EXPORTS = ["hp_plan_create", "hp_plan_create_host", "hp_plan_create_batched", "hp_plan_destroy",
            "hp_plan_query", "hp_plan_src_rows", "hp_plan_segments", "hp_plan_get_launch",
-           "hp_plan_set_launch", "hp_plan_tune", "hp_forward", "hp_backward",
+           "hp_plan_set_launch", "hp_plan_tune", "hp_forward", "hp_backward", "hp_backward_accumulate",
            "hp_set_option", "hp_get_option", "hp_probe_stream", "hp_profile_enable", "hp_profile_read",
            "hp_strerror", "hp_last_hip_error", "hp_version"]
 
@@ -98,6 +98,8 @@ def _lib():
     L.hp_plan_segments.argtypes = [vp, C.POINTER(hp_segment_t), i32]
     L.hp_forward.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp]
     L.hp_backward.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp]
+    L.hp_backward_accumulate.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp]
+    L.hp_backward_accumulate.restype = C.c_int
     L.hp_set_option.argtypes = [C.c_char_p, i64]
     L.hp_get_option.argtypes = [C.c_char_p]
     L.hp_get_option.restype = i64
@@ -135,7 +137,7 @@ def _i32p(a: Optional[np.ndarray]):
 def _token_map(m: TokenMap):
     keep = [np.ascontiguousarray(x, dtype=np.int32) for x in (m.img_sample, m.img_start, m.img_len)]
     dp = None if m.img_src_dp is None else np.ascontiguousarray(m.img_src_dp, dtype=np.int32)
-    t = hp_token_map_t(m.batch, m.seq, m.hidden, 0, m.n_images,
+    t = hp_token_map_t(m.batch, m.seq, m.hidden, int(getattr(m, "dtype", 0)), m.n_images,
                        _i32p(keep[0]), _i32p(keep[1]), _i32p(keep[2]), _i32p(dp))
     return t, (keep, dp)
 
@@ -207,6 +209,7 @@ class Plan:
         del keep
         self.info = hp_plan_info_t()
         _check(L.hp_plan_query(self._h, C.byref(self.info)), "hp_plan_query")
+        self.elem_bytes = self.info.row_bytes // self.hidden
 
     def get_launch(self, direction: int) -> dict:
         out = hp_launch_t()
@@ -244,23 +247,24 @@ class Plan:
         return [arr[i] for i in range(n)]
 
     # -- marshalling --------------------------------------------------------
-    def _pointers(self, tensors: Sequence, rows: Sequence[int], what: str):
+    def _pointers(self, tensors: Sequence, rows: Sequence[int], what: str, esize: Optional[int] = None):
+        esize = esize or self.elem_bytes
         P = (C.c_void_p * len(tensors))()
         for i, (t, r) in enumerate(zip(tensors, rows)):
             if t is None:
                 P[i] = None
                 continue
-            if not t.is_cuda or not t.is_contiguous() or t.element_size() != 2:
-                raise ValueError(f"{what}[{i}]: need a contiguous 2-byte CUDA tensor")
+            if not t.is_cuda or not t.is_contiguous() or t.element_size() != esize:
+                raise ValueError(f"{what}[{i}]: need a contiguous CUDA tensor of {esize}-byte elements")
             if t.numel() < r * self.hidden:
                 raise ValueError(f"{what}[{i}]: {t.numel()} elements, plan needs {r * self.hidden}")
             P[i] = t.data_ptr() if t.numel() else None
         return P
 
-    def _src_dst(self, src_bufs, dst_bufs):
+    def _src_dst(self, src_bufs, dst_bufs, src_esize: Optional[int] = None):
         if len(src_bufs) != self.info.n_src_bufs or len(dst_bufs) != self.info.n_dst_bufs:
             raise ValueError("wrong number of buffers for this plan")
-        ps = self._pointers(src_bufs, self.src_rows(), "src")
+        ps = self._pointers(src_bufs, self.src_rows(), "src", src_esize)
         pd = self._pointers(dst_bufs, [self.info.dst_rows_per_buf] * len(dst_bufs), "dst")
         return ps, pd
 
@@ -271,6 +275,12 @@ class Plan:
     def backward(self, dst_grad_bufs: Sequence, src_grad_bufs: Sequence, stream=None) -> None:
         ps, pd = self._src_dst(src_grad_bufs, dst_grad_bufs)
         _check(_lib().hp_backward(self._h, pd, ps, _stream_handle(stream)), "hp_backward")
+
+    def backward_accumulate(self, dst_grad_bufs: Sequence, src_accum_bufs: Sequence, stream=None) -> None:
+        """src_accum_bufs: float32 accumulators [rows_i, hidden], added to in place."""
+        ps, pd = self._src_dst(src_accum_bufs, dst_grad_bufs, src_esize=4)
+        _check(_lib().hp_backward_accumulate(self._h, pd, ps, _stream_handle(stream)),
+               "hp_backward_accumulate")
 
     # raw-pointer variants for timing loops (pointer arrays prepared once)
     def pointer_arrays(self, src_bufs: Sequence, dst_bufs: Sequence):
@@ -317,3 +327,7 @@ def hp_forward(plan: Plan, src_bufs, dst_bufs, stream=None) -> None:
 
 def hp_backward(plan: Plan, dst_grad_bufs, src_grad_bufs, stream=None) -> None:
     plan.backward(dst_grad_bufs, src_grad_bufs, stream)
+
+
+def hp_backward_accumulate(plan: Plan, dst_grad_bufs, src_accum_bufs, stream=None) -> None:
+    plan.backward_accumulate(dst_grad_bufs, src_accum_bufs, stream)

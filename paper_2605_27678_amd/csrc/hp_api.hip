@@ -171,7 +171,7 @@ hp_forward_kernel(const BufTable bufs, const KParams k) {
 }
 
 // ---------------------------------------------------------------------------
-// backward: NREP destination-gradient copies -> fp32 fold -> bf16 -> source copies
+// backward: NREP destination-gradient copies -> fp32 fold -> source copies
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf16_hi(uint32_t w) { return __uint_as_float(w & 0xffff0000u); }
@@ -186,82 +186,97 @@ __device__ __forceinline__ uint32_t pack_bf16x2(float lo, float hi) {
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-// W = 32-bit words per lane chunk (4, 2 or 1); W == 0 means one bf16 per lane.
-template <int W> struct Chunk { typedef uint32_t type __attribute__((ext_vector_type(W))); };
-template <> struct Chunk<1> { typedef uint32_t type; };
-template <> struct Chunk<0> { typedef uint16_t type; };
+// A lane chunk of N bytes (16, 8, 4 or 2) as a register type.
+template <int N> struct Bytes { typedef uint32_t type __attribute__((ext_vector_type(N / 4))); };
+template <> struct Bytes<4> { typedef uint32_t type; };
+template <> struct Bytes<2> { typedef uint16_t type; };
+template <int N>
+__device__ __forceinline__ uint32_t get_word(const typename Bytes<N>::type &v, int j) {
+    if constexpr (N >= 8) return v[j];
+    else return (uint32_t)v;
+}
+template <int N>
+__device__ __forceinline__ void set_word(typename Bytes<N>::type &v, int j, uint32_t w) {
+    if constexpr (N >= 8) v[j] = w;
+    else v = (typename Bytes<N>::type)w;
+}
 
-template <int W>
-struct Fold {
-    typedef typename Chunk<W>::type V;
-    static constexpr int kElems = W == 0 ? 1 : 2 * W;
-    float acc[kElems];
-
-    __device__ __forceinline__ static uint32_t word(const V &v, int j) {
-        if constexpr (W >= 2) return v[j];
-        else return (uint32_t)v;
-    }
-    __device__ __forceinline__ void first(const V &v) {
-        if constexpr (W == 0) acc[0] = bf16_lo(v);
-        else {
+// E elements of dtype DT (HP_BF16 or HP_F32) <-> E binary32 values.
+template <int DT, int E>
+struct Elems {
+    static constexpr int kBytes = E * (DT == HP_F32 ? 4 : 2);
+    typedef typename Bytes<kBytes>::type V;
+    __device__ __forceinline__ static void unpack(const V &v, float (&x)[E]) {
+        if constexpr (DT == HP_F32) {
 #pragma unroll
-            for (int j = 0; j < W; ++j) { acc[2 * j] = bf16_lo(word(v, j)); acc[2 * j + 1] = bf16_hi(word(v, j)); }
-        }
-    }
-    __device__ __forceinline__ void add(const V &v) {
-        if constexpr (W == 0) acc[0] = acc[0] + bf16_lo(v);
-        else {
+            for (int j = 0; j < E; ++j) x[j] = __uint_as_float(get_word<kBytes>(v, j));
+        } else if constexpr (E == 1) {
+            x[0] = bf16_lo(get_word<kBytes>(v, 0));
+        } else {
 #pragma unroll
-            for (int j = 0; j < W; ++j) {
-                acc[2 * j] = acc[2 * j] + bf16_lo(word(v, j));
-                acc[2 * j + 1] = acc[2 * j + 1] + bf16_hi(word(v, j));
+            for (int j = 0; j < E / 2; ++j) {
+                x[2 * j] = bf16_lo(get_word<kBytes>(v, j));
+                x[2 * j + 1] = bf16_hi(get_word<kBytes>(v, j));
             }
         }
     }
-    __device__ __forceinline__ V result() const {
-        if constexpr (W == 0) return (uint16_t)(pack_bf16x2(acc[0], 0.f) & 0xffffu);
-        else if constexpr (W == 1) return pack_bf16x2(acc[0], acc[1]);
-        else {
-            V out;
+    __device__ __forceinline__ static V pack(const float (&x)[E]) {
+        V v;
+        if constexpr (DT == HP_F32) {
 #pragma unroll
-            for (int j = 0; j < W; ++j) out[j] = pack_bf16x2(acc[2 * j], acc[2 * j + 1]);
-            return out;
+            for (int j = 0; j < E; ++j) set_word<kBytes>(v, j, __float_as_uint(x[j]));
+        } else if constexpr (E == 1) {
+            set_word<kBytes>(v, 0, pack_bf16x2(x[0], 0.f) & 0xffffu);
+        } else {
+#pragma unroll
+            for (int j = 0; j < E / 2; ++j) set_word<kBytes>(v, j, pack_bf16x2(x[2 * j], x[2 * j + 1]));
         }
+        return v;
     }
 };
 
-// U chunks per lane starting at chunk `done`, straight-line: the loads of all
-// replicas (groups of four when the replica count is only known at run time) are
-// issued before the first add.  GUARD as in forward_group.
-template <int W, int NREP, int U, bool GUARD, bool NTL, bool NTS>
+// U chunks of E elements per lane starting at chunk `done`, straight-line: the
+// loads of all replicas (groups of four when the replica count is only known at
+// run time) are issued before the first add.  GUARD as in forward_group.
+// ACC = false: the folded sum is rounded to the gradients' dtype and overwrites
+// the source-gradient rows.  ACC = true: the source side holds binary32
+// accumulators; the folded sum is added to them (one more binary32 add).
+template <int DT, int E, bool ACC, int NREP, int U, bool GUARD, bool NTL, bool NTS>
 __device__ __forceinline__ void backward_group(const BufTable &bufs, const KParams &k, const TileView &t,
                                                uint32_t nrep, uint32_t done, uint32_t n) {
-    typedef typename Chunk<W>::type V;
+    typedef Elems<DT, E> In;
+    typedef Elems<ACC ? HP_F32 : DT, E> Out;
+    typedef typename In::V VI;
+    typedef typename Out::V VO;
     constexpr int G = NREP > 0 ? NREP : 4;
+    constexpr uint32_t kElemBytes = DT == HP_F32 ? 4 : 2;
     const bool dense = t.pitch_rows == 1;
     const uint64_t pitch = (uint64_t)t.pitch_rows * k.row_bytes;
-    uint32_t i[U];
+    uint32_t i[U], ic[U];
     uint64_t goff[U];
 #pragma unroll
     for (int u = 0; u < U; ++u) {
         i[u] = done + u * blockDim.x + threadIdx.x;
-        const uint32_t byte = (GUARD ? min(i[u], n - 1) : i[u]) * (uint32_t)sizeof(V);
+        ic[u] = GUARD ? min(i[u], n - 1) : i[u];
+        const uint32_t byte = ic[u] * (uint32_t)In::kBytes;
         if (dense) goff[u] = byte;
         else {
             const uint32_t row = byte / k.row_bytes;
             goff[u] = row * pitch + (byte - row * k.row_bytes);
         }
     }
-    Fold<W> f[U];
+    // source-side offset of this tile in the output dtype
+    const uint64_t out_off = ACC ? t.src_off / kElemBytes * 4 : t.src_off;
+    float acc[U][E];
     for (uint32_t r0 = 0; r0 < nrep; r0 += G) {
-        V v[G][U];
+        VI v[G][U];
 #pragma unroll
         for (int g = 0; g < G; ++g) {
             // past the last replica of a run-time count: re-read the last one, result unused
             const uint32_t r = NREP > 0 ? r0 + g : min(r0 + g, nrep - 1);
             const char *gp = (const char *)bufs.p[k.dst_base + t.dst_buf0 + r] + t.dst_off;
 #pragma unroll
-            for (int u = 0; u < U; ++u) v[g][u] = ld<V, NTL>((const V *)(gp + goff[u]));
+            for (int u = 0; u < U; ++u) v[g][u] = ld<VI, NTL>((const VI *)(gp + goff[u]));
         }
         // ascending tp: copy 0 starts the accumulator, copies 1.. are added in order
 #pragma unroll
@@ -269,38 +284,57 @@ __device__ __forceinline__ void backward_group(const BufTable &bufs, const KPara
             if (NREP > 0 || r0 + g < nrep) {
 #pragma unroll
                 for (int u = 0; u < U; ++u) {
-                    if (g == 0 && r0 == 0) f[u].first(v[g][u]); else f[u].add(v[g][u]);
+                    float x[E];
+                    In::unpack(v[g][u], x);
+#pragma unroll
+                    for (int e = 0; e < E; ++e) acc[u][e] = (g == 0 && r0 == 0) ? x[e] : acc[u][e] + x[e];
                 }
             }
         }
     }
-    V res[U];
+    if constexpr (!ACC) {
+        VO res[U];
 #pragma unroll
-    for (int u = 0; u < U; ++u) res[u] = f[u].result();
-    for (uint32_t s = 0; s < k.src_copies; ++s) {
-        char *out = (char *)bufs.p[t.src_buf + s] + t.src_off;
+        for (int u = 0; u < U; ++u) res[u] = Out::pack(acc[u]);
+        for (uint32_t s = 0; s < k.src_copies; ++s) {
+            char *out = (char *)bufs.p[t.src_buf + s] + out_off;
 #pragma unroll
-        for (int u = 0; u < U; ++u)
-            if (!GUARD || i[u] < n) st<V, NTS>((V *)out + i[u], res[u]);
+            for (int u = 0; u < U; ++u)
+                if (!GUARD || i[u] < n) st<VO, NTS>((VO *)out + i[u], res[u]);
+        }
+    } else {
+        for (uint32_t s = 0; s < k.src_copies; ++s) {
+            char *out = (char *)bufs.p[t.src_buf + s] + out_off;
+            VO old[U];
+#pragma unroll
+            for (int u = 0; u < U; ++u) old[u] = ld<VO, NTL>((const VO *)out + ic[u]);
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+                float x[E];
+                Out::unpack(old[u], x);
+#pragma unroll
+                for (int e = 0; e < E; ++e) x[e] = x[e] + acc[u][e];
+                if (!GUARD || i[u] < n) st<VO, NTS>((VO *)out + i[u], Out::pack(x));
+            }
+        }
     }
 }
 
-template <int W, int NREP, bool NTL, bool NTS>
+template <int DT, int E, bool ACC, int NREP, bool NTL, bool NTS>
 __global__ void __launch_bounds__(1024)
 hp_backward_kernel(const BufTable bufs, const KParams k) {
-    typedef typename Chunk<W>::type V;
     const TileView t = locate_tile(k, blockIdx.x);
     const uint32_t nrep = NREP > 0 ? (uint32_t)NREP : k.dst_copies;
-    const uint32_t n = t.nbytes / (uint32_t)sizeof(V);      // lane chunks in this tile, >= 1
+    const uint32_t n = t.nbytes / (uint32_t)Elems<DT, E>::kBytes;   // lane chunks in this tile, >= 1
     const uint32_t step = blockDim.x;
-    uint32_t done = 0;                                       // uniform
+    uint32_t done = 0;                                               // uniform
     for (; n - done >= 2 * step; done += 2 * step)
-        backward_group<W, NREP, 2, false, NTL, NTS>(bufs, k, t, nrep, done, n);
+        backward_group<DT, E, ACC, NREP, 2, false, NTL, NTS>(bufs, k, t, nrep, done, n);
     if (n - done >= step) {
-        backward_group<W, NREP, 1, false, NTL, NTS>(bufs, k, t, nrep, done, n);
+        backward_group<DT, E, ACC, NREP, 1, false, NTL, NTS>(bufs, k, t, nrep, done, n);
         done += step;
     }
-    if (n - done > 0) backward_group<W, NREP, 1, true, NTL, NTS>(bufs, k, t, nrep, done, n);
+    if (n - done > 0) backward_group<DT, E, ACC, NREP, 1, true, NTL, NTS>(bufs, k, t, nrep, done, n);
 }
 
 // ---------------------------------------------------------------------------
@@ -415,18 +449,6 @@ unsigned lds_for_cap(int block, int waves_per_cu) {
     return (unsigned)std::min(lds, 64 * 1024);
 }
 
-// Largest chunk width in {16, 8, 4, 2} bytes that divides the row size and
-// every pointer the launch will touch.
-int pick_width(const hp_plan *p, const BufTable &bt, int n_ptrs) {
-    uint64_t bits = (uint64_t)p->row_bytes;
-    for (int i = 0; i < n_ptrs; ++i) bits |= (uint64_t)(uintptr_t)bt.p[i];
-    if ((bits & 15) == 0) return 16;
-    if ((bits & 7) == 0) return 8;
-    if ((bits & 3) == 0) return 4;
-    if ((bits & 1) == 0) return 2;
-    return 0;
-}
-
 template <typename V, bool NTL, bool NTS>
 void launch_forward_nrep(int copies, const LaunchCfg &c, const BufTable &bt, const KParams &k) {
     switch (copies) {
@@ -442,37 +464,49 @@ template <bool NTL, bool NTS>
 void launch_forward_width(int width, int copies, const LaunchCfg &c, const BufTable &bt, const KParams &k) {
     switch (width) {
         case 16: launch_forward_nrep<u32x4, NTL, NTS>(copies, c, bt, k); break;
-        case 8: launch_forward_nrep<u32x2, NTL, NTS>(copies, c, bt, k); break;
         case 4: launch_forward_nrep<uint32_t, NTL, NTS>(copies, c, bt, k); break;
         default: launch_forward_nrep<uint16_t, NTL, NTS>(copies, c, bt, k); break;
     }
 }
 
-template <int W, bool NTL, bool NTS>
+template <int DT, int E, bool ACC, bool NTL, bool NTS>
 void launch_backward_nrep(int copies, const LaunchCfg &c, const BufTable &bt, const KParams &k) {
     switch (copies) {
-        case 1: HP_LAUNCH((hp_backward_kernel<W, 1, NTL, NTS>), c, bt, k); break;
-        case 2: HP_LAUNCH((hp_backward_kernel<W, 2, NTL, NTS>), c, bt, k); break;
-        case 4: HP_LAUNCH((hp_backward_kernel<W, 4, NTL, NTS>), c, bt, k); break;
-        case 8: HP_LAUNCH((hp_backward_kernel<W, 8, NTL, NTS>), c, bt, k); break;
-        default: HP_LAUNCH((hp_backward_kernel<W, 0, NTL, NTS>), c, bt, k); break;
+        case 1: HP_LAUNCH((hp_backward_kernel<DT, E, ACC, 1, NTL, NTS>), c, bt, k); break;
+        case 2: HP_LAUNCH((hp_backward_kernel<DT, E, ACC, 2, NTL, NTS>), c, bt, k); break;
+        case 4: HP_LAUNCH((hp_backward_kernel<DT, E, ACC, 4, NTL, NTS>), c, bt, k); break;
+        case 8: HP_LAUNCH((hp_backward_kernel<DT, E, ACC, 8, NTL, NTS>), c, bt, k); break;
+        default: HP_LAUNCH((hp_backward_kernel<DT, E, ACC, 0, NTL, NTS>), c, bt, k); break;
     }
 }
 
+// `elems` = elements per lane chunk, chosen by backward_elems().
 template <bool NTL, bool NTS>
-void launch_backward_width(int width, int copies, const LaunchCfg &c, const BufTable &bt, const KParams &k) {
-    switch (width) {
-        case 16: launch_backward_nrep<4, NTL, NTS>(copies, c, bt, k); break;
-        case 8: launch_backward_nrep<2, NTL, NTS>(copies, c, bt, k); break;
-        case 4: launch_backward_nrep<1, NTL, NTS>(copies, c, bt, k); break;
-        default: launch_backward_nrep<0, NTL, NTS>(copies, c, bt, k); break;
+void launch_backward_shape(int dtype, bool acc, int elems, int copies, const LaunchCfg &c, const BufTable &bt,
+                           const KParams &k) {
+    if (dtype == HP_F32) {
+        if (elems == 4) {
+            if (acc) launch_backward_nrep<HP_F32, 4, true, NTL, NTS>(copies, c, bt, k);
+            else launch_backward_nrep<HP_F32, 4, false, NTL, NTS>(copies, c, bt, k);
+        } else {
+            if (acc) launch_backward_nrep<HP_F32, 1, true, NTL, NTS>(copies, c, bt, k);
+            else launch_backward_nrep<HP_F32, 1, false, NTL, NTS>(copies, c, bt, k);
+        }
+    } else if (acc) {
+        if (elems == 4) launch_backward_nrep<HP_BF16, 4, true, NTL, NTS>(copies, c, bt, k);
+        else launch_backward_nrep<HP_BF16, 1, true, NTL, NTS>(copies, c, bt, k);
+    } else {
+        if (elems == 8) launch_backward_nrep<HP_BF16, 8, false, NTL, NTS>(copies, c, bt, k);
+        else if (elems == 2) launch_backward_nrep<HP_BF16, 2, false, NTL, NTS>(copies, c, bt, k);
+        else launch_backward_nrep<HP_BF16, 1, false, NTL, NTS>(copies, c, bt, k);
     }
 }
 
-enum Direction { kForward = 0, kBackward = 1 };
+enum Direction { kForward = 0, kBackward = 1, kBackwardAcc = 2 };
 
-// Enqueues one kernel for direction `dir` with launch shape `L`.
-int enqueue(const hp_plan *p, Direction dir, const hp::Launch &L, const BufTable &bt, int width,
+// Enqueues one kernel for direction `dir` with launch shape `L`.  `lane` is the
+// lane chunk chosen by prepare(): bytes for forward, elements for backward.
+int enqueue(const hp_plan *p, Direction dir, const hp::Launch &L, const BufTable &bt, int lane,
             hipStream_t stream, EventPair ev) {
     const size_t n_seg = p->segments.size();
     KParams k;
@@ -494,17 +528,18 @@ int enqueue(const hp_plan *p, Direction dir, const hp::Launch &L, const BufTable
     const int nt = L.nontemporal & 3, copies = p->dst_copies;
     if (dir == kForward) {
         switch (nt) {
-            case 0: launch_forward_width<false, false>(width, copies, c, bt, k); break;
-            case 1: launch_forward_width<true, false>(width, copies, c, bt, k); break;
-            case 2: launch_forward_width<false, true>(width, copies, c, bt, k); break;
-            default: launch_forward_width<true, true>(width, copies, c, bt, k); break;
+            case 0: launch_forward_width<false, false>(lane, copies, c, bt, k); break;
+            case 1: launch_forward_width<true, false>(lane, copies, c, bt, k); break;
+            case 2: launch_forward_width<false, true>(lane, copies, c, bt, k); break;
+            default: launch_forward_width<true, true>(lane, copies, c, bt, k); break;
         }
     } else {
+        const bool acc = dir == kBackwardAcc;
         switch (nt) {
-            case 0: launch_backward_width<false, false>(width, copies, c, bt, k); break;
-            case 1: launch_backward_width<true, false>(width, copies, c, bt, k); break;
-            case 2: launch_backward_width<false, true>(width, copies, c, bt, k); break;
-            default: launch_backward_width<true, true>(width, copies, c, bt, k); break;
+            case 0: launch_backward_shape<false, false>(p->dtype, acc, lane, copies, c, bt, k); break;
+            case 1: launch_backward_shape<true, false>(p->dtype, acc, lane, copies, c, bt, k); break;
+            case 2: launch_backward_shape<false, true>(p->dtype, acc, lane, copies, c, bt, k); break;
+            default: launch_backward_shape<true, true>(p->dtype, acc, lane, copies, c, bt, k); break;
         }
     }
     if (hip_failed(hipGetLastError())) return HP_EHIP;
@@ -513,10 +548,13 @@ int enqueue(const hp_plan *p, Direction dir, const hp::Launch &L, const BufTable
 
 // Fills the pointer table and checks what the kernels assume: every buffer a
 // segment touches is present, and the plan's tables live on the current device.
-// `all_src_copies` is false for forward (only copy tp = 0 of a source rank is
-// read) and true for backward (every copy is written).
-int prepare(const hp_plan *p, const void *const *src, const void *const *dst, bool all_src_copies,
-            BufTable *bt, int *width) {
+// Forward reads only copy tp = 0 of a source rank; the backward directions
+// write every copy.  *lane receives the widest lane chunk that the row size and
+// every pointer allow: bytes (16, 4 or the element size) for forward, elements
+// for backward (the binary32 accumulators of kBackwardAcc are addressed in
+// 16-byte or 4-byte chunks).
+int prepare(const hp_plan *p, Direction dir, const void *const *src, const void *const *dst,
+            BufTable *bt, int *lane) {
     if (!p || !src || !dst) return HP_EINVAL;
     if (p->segments.empty()) return HP_OK;
     if (!p->d_segs) return HP_ESTATE;
@@ -525,17 +563,32 @@ int prepare(const hp_plan *p, const void *const *src, const void *const *dst, bo
     if (dev != p->device) return HP_ESTATE;
     std::memset(bt, 0, sizeof(*bt));
     int n = 0;
+    uint64_t src_bits = 0, dst_bits = (uint64_t)p->row_bytes;
     for (int i = 0; i < p->n_src_bufs; ++i) {
-        const bool needed = p->src_rows[i] > 0 && (all_src_copies || i % p->src_copies == 0);
+        const bool needed = p->src_rows[i] > 0 && (dir != kForward || i % p->src_copies == 0);
         if (needed && !src[i]) return HP_EINVAL;
         bt->p[n++] = needed ? const_cast<void *>(src[i]) : nullptr;
+        if (needed) src_bits |= (uint64_t)(uintptr_t)src[i];
     }
     for (int j = 0; j < p->n_dst_bufs; ++j) {
         if (!dst[j]) return HP_EINVAL;
         bt->p[n++] = const_cast<void *>(dst[j]);
+        dst_bits |= (uint64_t)(uintptr_t)dst[j];
     }
-    *width = pick_width(p, *bt, n);
-    if (*width == 0) return HP_EALIGN;
+    const uint64_t eb = (uint64_t)p->elem_bytes;
+    if (dir == kBackwardAcc) {
+        if (((dst_bits & (4 * eb - 1)) | (src_bits & 15)) == 0) *lane = 4;
+        else if (((dst_bits & (eb - 1)) | (src_bits & 3)) == 0) *lane = 1;
+        else return HP_EALIGN;
+    } else {
+        const uint64_t bits = src_bits | dst_bits;
+        int width;
+        if ((bits & 15) == 0) width = 16;
+        else if ((bits & 3) == 0) width = 4;
+        else if ((bits & (eb - 1)) == 0) width = (int)eb;
+        else return HP_EALIGN;
+        *lane = dir == kForward ? width : width / (int)eb;
+    }
     return HP_OK;
 }
 
@@ -774,7 +827,7 @@ int hp_plan_set_launch(hp_plan_t *p, int32_t direction, const hp_launch_t *in) {
 int hp_forward(const hp_plan_t *p, const void *const *src_bufs, void *const *dst_bufs, void *stream) {
     BufTable bt;
     int width = 0;
-    int rc = prepare(p, src_bufs, (const void *const *)dst_bufs, false, &bt, &width);
+    int rc = prepare(p, kForward, src_bufs, (const void *const *)dst_bufs, &bt, &width);
     if (rc != HP_OK || p->segments.empty()) return rc;
     return enqueue(p, kForward, p->fwd, bt, width, (hipStream_t)stream, next_event_pair(0));
 }
@@ -783,9 +836,18 @@ int hp_backward(const hp_plan_t *p, const void *const *dst_grad_bufs, void *cons
                 void *stream) {
     BufTable bt;
     int width = 0;
-    int rc = prepare(p, (const void *const *)src_grad_bufs, dst_grad_bufs, true, &bt, &width);
+    int rc = prepare(p, kBackward, (const void *const *)src_grad_bufs, dst_grad_bufs, &bt, &width);
     if (rc != HP_OK || p->segments.empty()) return rc;
     return enqueue(p, kBackward, p->bwd, bt, width, (hipStream_t)stream, next_event_pair(1));
+}
+
+int hp_backward_accumulate(const hp_plan_t *p, const void *const *dst_grad_bufs, void *const *src_accum_bufs,
+                           void *stream) {
+    BufTable bt;
+    int lane = 0;
+    int rc = prepare(p, kBackwardAcc, (const void *const *)src_accum_bufs, dst_grad_bufs, &bt, &lane);
+    if (rc != HP_OK || p->segments.empty()) return rc;
+    return enqueue(p, kBackwardAcc, p->bwd, bt, lane, (hipStream_t)stream, next_event_pair(2));
 }
 
 int hp_plan_tune(hp_plan_t *p, const void *const *src_bufs, void *const *dst_bufs,
@@ -797,11 +859,11 @@ int hp_plan_tune(hp_plan_t *p, const void *const *src_bufs, void *const *dst_buf
     BufTable bt;
     int width = 0, rc = HP_OK;
     if (src_bufs) {
-        rc = prepare(p, src_bufs, (const void *const *)dst_bufs, false, &bt, &width);
+        rc = prepare(p, kForward, src_bufs, (const void *const *)dst_bufs, &bt, &width);
         if (rc == HP_OK) rc = tune_direction(p, kForward, bt, width, (hipStream_t)stream);
     }
     if (rc == HP_OK && dst_grad_bufs) {
-        rc = prepare(p, (const void *const *)src_grad_bufs, dst_grad_bufs, true, &bt, &width);
+        rc = prepare(p, kBackward, (const void *const *)src_grad_bufs, dst_grad_bufs, &bt, &width);
         if (rc == HP_OK) rc = tune_direction(p, kBackward, bt, width, (hipStream_t)stream);
     }
     return rc;

@@ -90,7 +90,7 @@ int validate(const hp_layout_t *src, const hp_layout_t *dst, const hp_token_map_
         if (g->row_order != HP_ROW_BSH && g->row_order != HP_ROW_SBH) return HP_EINVAL;
     }
     if (m->batch < 1 || m->seq < 1 || m->hidden < 1 || m->n_images < 0) return HP_EINVAL;
-    if (m->dtype != HP_BF16) return HP_EINVAL;
+    if (m->dtype != HP_BF16 && m->dtype != HP_F32) return HP_EINVAL;
     if (m->n_images > 0 && (!m->img_sample || !m->img_start || !m->img_len)) return HP_EINVAL;
 
     // the encoder side has no context parallelism and plain replicated TP
@@ -189,7 +189,7 @@ int build_host_plan(const hp_layout_t *src, const hp_layout_t *dst,
     p->dst = *dst;
     p->batch = m0->batch; p->seq = m0->seq; p->hidden = m0->hidden; p->dtype = m0->dtype;
     p->n_maps = n_maps;
-    p->elem_bytes = 2;
+    p->elem_bytes = m0->dtype == HP_F32 ? 4 : 2;
     p->row_bytes = (int64_t)m0->hidden * p->elem_bytes;
     if (p->row_bytes > (int64_t)1 << 24) return HP_ELAYOUT;       // a tile holds whole rows in 32 bits
     const int32_t src_per_map = src->tp * src->dp;

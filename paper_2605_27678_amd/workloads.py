@@ -26,6 +26,8 @@ CP_CONTIGUOUS = 0
 CP_ZIGZAG = 1
 ROW_BSH = 0
 ROW_SBH = 1
+DT_BF16 = 0
+DT_F32 = 1
 
 BASE_SEED = 276780
 
@@ -60,6 +62,7 @@ class TokenMap:
     img_start: np.ndarray
     img_len: np.ndarray
     img_src_dp: Optional[np.ndarray] = None
+    dtype: int = DT_BF16
 
     def __post_init__(self):
         self.img_sample = np.ascontiguousarray(self.img_sample, dtype=np.int32)

@@ -90,3 +90,57 @@ def check_case(src_grid, dst_grid, tm, seed=1, gen_device="cpu", stream=None, ch
     info = plan.info
     plan.close()
     return info
+
+
+def check_case_extended(src_grid, dst_grid, tm, seed=1):
+    """binary32 payloads (forward, backward) and the accumulating backward for
+    the token map's dtype, bit for bit against the oracle."""
+    dev = "cuda:0"
+    is_f32 = tm.dtype == wl.DT_F32
+    tdt, ndt = (torch.float32, np.float32) if is_f32 else (torch.bfloat16, np.uint16)
+    plan = hp.hp_plan_create(src_grid, dst_grid, tm)
+    prob = oracle.Problem(src_grid, dst_grid, tm)
+    H, rows, drows = tm.hidden, prob.src_rows(), prob.dst_rows()
+
+    def rnd(shape, s):
+        g = torch.Generator().manual_seed(s)
+        e = torch.randint(-10, 10, shape, generator=g).float()
+        return (torch.randn(shape, generator=g) * torch.exp2(e)).to(tdt)
+
+    def host(t):
+        t = t.cpu().contiguous()
+        return t.numpy().copy() if is_f32 else t.view(torch.int16).numpy().view(np.uint16).copy()
+
+    src = [rnd((r, H), seed * 31 + i) for i, r in enumerate(rows)]
+    pre = [rnd((drows, H), seed * 31 + 100 + j) for j in range(prob.n_dst)]
+    grads = [rnd((drows, H), seed * 31 + 200 + j) for j in range(prob.n_dst)]
+    acc0 = [torch.randn((r, H), generator=torch.Generator().manual_seed(seed * 31 + 300 + i)) for i, r in enumerate(rows)]
+
+    g_dst = [t.to(dev) for t in pre]
+    g_grads = [t.to(dev) for t in grads]
+    if is_f32:                                              # the bf16 forward/backward are covered by check_case
+        hp.hp_forward(plan, [t.to(dev) for t in src], g_dst)
+        g_sg = [torch.full((r, H), float("nan"), dtype=tdt, device=dev) for r in rows]
+        hp.hp_backward(plan, g_grads, g_sg)
+    g_acc = [t.to(dev) for t in acc0]
+    hp.hp_backward_accumulate(plan, g_grads, g_acc)
+    hp.hp_backward_accumulate(plan, g_grads, g_acc)          # twice: really read-modify-write
+    torch.cuda.synchronize()
+
+    if is_f32:
+        o_dst = [host(t) for t in pre]
+        prob.forward([host(t) for t in src], o_dst)
+        for j in range(prob.n_dst):
+            assert np.array_equal(host(g_dst[j]).view(np.uint32), o_dst[j].view(np.uint32)), f"f32 forward, buffer {j}"
+        o_sg = [np.full((r, H), np.nan, np.float32) for r in rows]
+        prob.backward_f32([host(t) for t in grads], o_sg)
+        for i in range(prob.n_src):
+            assert np.array_equal(host(g_sg[i]).view(np.uint32), o_sg[i].view(np.uint32)), f"f32 backward, buffer {i}"
+    o_acc = [t.numpy().copy() for t in acc0]
+    hg = [host(t) for t in grads]
+    prob.backward_accumulate(hg, o_acc)
+    prob.backward_accumulate(hg, o_acc)
+    for i in range(prob.n_src):
+        got = g_acc[i].cpu().numpy()
+        assert np.array_equal(got.view(np.uint32), o_acc[i].view(np.uint32)), f"accumulate, buffer {i}"
+    plan.close()

@@ -339,3 +339,29 @@ def test_stream_probe_reports_a_rate():
     assert gbps2 > 50.0 and shape2 == fixed
     with pytest.raises(hp.HpError):
         hp.hp_probe_stream(9, 1, 8 << 20)
+
+
+# ---- binary32 payloads and the accumulating backward ---------------------------
+
+@pytest.mark.parametrize("seed", range(12))
+def test_f32_and_accumulate_random_layouts(seed):
+    from parity import check_case_extended
+    rng = np.random.default_rng(700 + seed)
+    src, dst, tm = wl.random_layout_case(rng)
+    check_case_extended(src, dst, replace(tm, dtype=wl.DT_F32), seed=seed)
+    check_case_extended(src, dst, tm, seed=seed)                     # bf16 gradients into f32 accumulators
+
+
+@pytest.mark.parametrize("hidden,dtype", [(7, 0), (7, 1), (12, 0), (320, 0), (320, 1), (1022, 0), (2560, 1)])
+def test_f32_and_accumulate_long_context_spans(hidden, dtype):
+    from parity import check_case_extended
+    w = wl.long_context(n_images=9)
+    check_case_extended(w.src, w.dst, replace(w.maps[0], hidden=hidden, dtype=dtype), seed=hidden)
+
+
+def test_accumulate_large_scale_replicas():
+    """TP_dst = 8, TP_src = 2 (both source copies accumulate), hidden 96."""
+    from parity import check_case_extended
+    w = wl.scaled(wl.large_scale(), 96)
+    check_case_extended(w.src, w.dst, w.maps[0], seed=9)
+    check_case_extended(w.src, w.dst, replace(w.maps[0], dtype=wl.DT_F32), seed=10)

@@ -518,3 +518,85 @@ def test_named_workloads_have_the_stated_shapes():
                 s, l = m.img_start[sel].astype(np.int64), m.img_len[sel].astype(np.int64)
                 o = np.argsort(s)
                 assert np.all(s[o][1:] >= (s[o] + l[o])[:-1]) and np.all(s + l <= m.seq) and np.all(s >= 0)
+
+
+# ----------------------------------------------------------------------------
+# binary32 gradients and accumulating output
+# ----------------------------------------------------------------------------
+
+def test_generic_backward_agrees_with_the_bf16_backward():
+    """orc_backward(dtype=bf16, overwrite) is the same computation as
+    orc_backward_bf16 (which the fixtures above pin)."""
+    rng = np.random.default_rng(21)
+    for _ in range(10):
+        src, dst, tm = wl.random_layout_case(rng)
+        prob = oracle.Problem(src, dst, tm)
+        e = rng.integers(-12, 12, size=(prob.n_dst, prob.dst_rows(), tm.hidden))
+        g = [_f2b((rng.standard_normal((prob.dst_rows(), tm.hidden)) * np.exp2(e[j])).astype(np.float32))
+             for j in range(prob.n_dst)]
+        a = [np.full((r, tm.hidden), 0x7FC1, np.uint16) for r in prob.src_rows()]
+        b = [np.full((r, tm.hidden), 0x7FC1, np.uint16) for r in prob.src_rows()]
+        prob.backward_bf16(g, a)
+        prob._backward(0, False, g, b)
+        assert all(np.array_equal(x, y) for x, y in zip(a, b))
+
+
+def test_f32_backward_fold_order_and_tp2_is_numpy_add():
+    g = json.load(open(os.path.join(GOLDEN, "bf16_rounding.json")))
+    tm = wl.TokenMap(1, 1, 1, [0], [0], [1])
+    for case in g["fold"][:3]:                       # the order-sensitive binary32 cases
+        terms = case["terms"]
+        prob = oracle.Problem(wl.Grid(), wl.Grid(tp=len(terms)), tm)
+        out = [np.zeros((1, 1), np.float32)]
+        prob.backward_f32([np.array([[t]], np.float32) for t in terms], out)
+        assert float(out[0][0, 0]) == float(case["result"]), case["why"]
+    # no rounding to bf16: 1 + 2^-8 stays
+    prob = oracle.Problem(wl.Grid(), wl.Grid(tp=2), tm)
+    out = [np.zeros((1, 1), np.float32)]
+    prob.backward_f32([np.array([[1.0]], np.float32), np.array([[2.0 ** -8]], np.float32)], out)
+    assert float(out[0][0, 0]) == 1.00390625
+    # two replicas on a random layout: one numpy float32 add, routed by the forward map
+    rng = np.random.default_rng(22)
+    tm = wl.token_map_from_lens(rng, 1, 64, 16, [[5, 9, 17]])
+    src, dst = wl.Grid(tp=2, dp=2), wl.Grid(tp=2, cp=2, cp_split=wl.CP_ZIGZAG)
+    prob = oracle.Problem(src, dst, tm)
+    gf = [(rng.standard_normal((prob.dst_rows(), 16)) * np.exp2(rng.integers(-20, 20, size=(prob.dst_rows(), 16)))).astype(np.float32)
+          for _ in range(prob.n_dst)]
+    sg = [np.full((r, 16), np.nan, np.float32) for r in prob.src_rows()]
+    prob.backward_f32(gf, sg)
+    for j in range(0, prob.n_dst, 2):
+        sb, sr = prob.forward_map(j)
+        want = gf[j] + gf[j + 1]
+        for r in np.nonzero(sb >= 0)[0]:
+            for ts in range(2):
+                assert np.array_equal(sg[sb[r] + ts][sr[r]], want[r])
+    assert not any(np.isnan(a).any() for a in sg)
+
+
+def test_accumulate_adds_the_fold_to_what_is_there():
+    """acc_out = acc_in + fold(replicas): shown on small integers (exact), on a
+    case where the extra add rounds (2^24 accumulator + 1), and applied twice."""
+    rng = np.random.default_rng(23)
+    for dtype in (0, 1):
+        src, dst, tm = wl.random_layout_case(rng)
+        prob = oracle.Problem(src, dst, tm)
+        gi = [rng.integers(-8, 9, size=(prob.dst_rows(), tm.hidden)).astype(np.float32) for _ in range(prob.n_dst)]
+        g = [_f2b(x) for x in gi] if dtype == 0 else gi
+        start = [rng.integers(-50, 50, size=(r, tm.hidden)).astype(np.float32) for r in prob.src_rows()]
+        acc = [a.copy() for a in start]
+        prob.backward_accumulate(g, acc)
+        once = [np.zeros_like(a) for a in start]
+        (prob.backward_f32 if dtype == 1 else (lambda gg, out: prob._backward(0, True, gg, out)))(g, once)
+        for a, s, o in zip(acc, start, once):
+            assert np.array_equal(a, s + o)                  # integers: exact
+        prob.backward_accumulate(g, acc)
+        for a, s, o in zip(acc, start, once):
+            assert np.array_equal(a, s + 2 * o)
+    tm = wl.TokenMap(1, 1, 1, [0], [0], [1])
+    prob = oracle.Problem(wl.Grid(), wl.Grid(tp=2), tm)
+    acc = [np.array([[16777216.0]], np.float32)]
+    prob.backward_accumulate([_f2b([[0.5]]), _f2b([[0.5]])], acc)     # fold = 1 exactly; 2^24 + 1 ties to even
+    assert float(acc[0][0, 0]) == 16777216.0
+    acc = [np.array([[16777216.0]], np.float32)]
+    prob.backward_accumulate([_f2b([[1.0]]), _f2b([[1.0]])], acc)     # fold = 2; 2^24 + 2 is exact
+    assert float(acc[0][0, 0]) == 16777218.0
