@@ -365,3 +365,59 @@ def test_accumulate_large_scale_replicas():
     w = wl.scaled(wl.large_scale(), 96)
     check_case_extended(w.src, w.dst, w.maps[0], seed=9)
     check_case_extended(w.src, w.dst, replace(w.maps[0], dtype=wl.DT_F32), seed=10)
+
+
+# ---- batch-shard cases of the figures and joins of several edges ----------------
+
+@pytest.mark.parametrize("dp_src,dp_dst", [(4, 2), (2, 4), (4, 4), (8, 1), (1, 4)])
+def test_fan_in_fan_out_equal_dp(dp_src, dp_dst):
+    """Fan-in (DP_src > DP_dst), fan-out (DP_src < DP_dst) and equal DP with
+    different TP widths on the two sides, several samples per rank."""
+    rng = np.random.default_rng(dp_src * 10 + dp_dst)
+    batch = 8
+    tm = wl.token_map_from_lens(rng, batch, 48, 40, [[int(x) for x in rng.integers(1, 9, size=3)] for _ in range(batch)])
+    check_case(wl.Grid(tp=2, dp=dp_src), wl.Grid(tp=3, cp=2, dp=dp_dst, cp_split=wl.CP_ZIGZAG), tm, seed=dp_src)
+    check_case(wl.Grid(tp=1, dp=dp_src), wl.Grid(tp=2, cp=1, dp=dp_dst, row_order=wl.ROW_SBH), tm, seed=dp_dst)
+
+
+def test_two_edges_join_in_one_sequence():
+    """Two encoders (say images and audio) feed disjoint spans of the same LLM
+    sequence through two plans, one per edge; backward routes each gradient
+    through the plan of the edge that produced the activation."""
+    rng = np.random.default_rng(77)
+    B, S, H = 2, 256, 64
+    dst = wl.Grid(tp=2, cp=2, dp=1, cp_split=wl.CP_ZIGZAG)
+    # interleave the two modalities' spans: even slots of 16 tokens to edge A, odd slots to edge B
+    slots = [(b, s) for b in range(B) for s in range(0, S, 16) if rng.random() < 0.6]
+    A = [x for i, x in enumerate(slots) if i % 2 == 0]
+    Bm = [x for i, x in enumerate(slots) if i % 2 == 1]
+    mk = lambda sp, ln: wl.TokenMap(B, S, H, [b for b, _ in sp], [s for _, s in sp], [ln] * len(sp))
+    tm_a, tm_b = mk(A, 16), mk(Bm, 11)
+    src_a, src_b = wl.Grid(tp=1, dp=4), wl.Grid(tp=2, dp=2, rank_offset=4)
+    pa, pb = hp.hp_plan_create(src_a, dst, tm_a), hp.hp_plan_create(src_b, dst, tm_b)
+    oa, ob = oracle.Problem(src_a, dst, tm_a), oracle.Problem(src_b, dst, tm_b)
+    xa = [wl.random_bf16((r, H), 1 + i) for i, r in enumerate(pa.src_rows())]
+    xb = [wl.random_bf16((r, H), 20 + i) for i, r in enumerate(pb.src_rows())]
+    pre = [wl.random_bf16((pa.info.dst_rows_per_buf, H), 40 + j) for j in range(4)]
+    g_dst = [t.cuda() for t in pre]
+    st = torch.cuda.Stream()
+    torch.cuda.synchronize()
+    hp.hp_forward(pa, [t.cuda() for t in xa], g_dst, st)
+    hp.hp_forward(pb, [t.cuda() for t in xb], g_dst, st)
+    grads = [wl.random_bf16((pa.info.dst_rows_per_buf, H), 60 + j, "cuda") for j in range(4)]
+    ga = [torch.zeros((r, H), dtype=torch.bfloat16, device="cuda") for r in pa.src_rows()]
+    gb = [torch.zeros((r, H), dtype=torch.bfloat16, device="cuda") for r in pb.src_rows()]
+    hp.hp_backward(pa, grads, ga, st)
+    hp.hp_backward(pb, grads, gb, st)
+    st.synchronize()
+    o_dst = [_to_host_bits(t).copy() for t in pre]
+    oa.forward([_to_host_bits(t) for t in xa], o_dst)
+    ob.forward([_to_host_bits(t) for t in xb], o_dst)
+    for j in range(4):
+        assert np.array_equal(_to_host_bits(g_dst[j]), o_dst[j])
+    hg = [_to_host_bits(t) for t in grads]
+    for prob, got in ((oa, ga), (ob, gb)):
+        want = [np.zeros((r, H), np.uint16) for r in prob.src_rows()]
+        prob.backward_bf16(hg, want)
+        for a, b in zip(got, want):
+            assert np.array_equal(_to_host_bits(a), b)
