@@ -55,6 +55,11 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-tune", action="store_true",
                     help="keep the default launch shapes instead of calling hp_plan_tune before the timed region")
+    ap.add_argument("--dtype", default="bf16", choices=["bf16", "f32"], help="payload element type")
+    ap.add_argument("--seq-shard", action="store_true",
+                    help="destination TP ranks hold sequence shards instead of replicas (sequence parallelism)")
+    ap.add_argument("--accumulate", action="store_true",
+                    help="backward adds into fp32 source accumulators (hp_backward_accumulate)")
     ap.add_argument("--per-microbatch", action="store_true",
                     help="one plan and one launch per microbatch instead of one batched plan")
     ap.add_argument("--option", action="append", default=[], metavar="KEY=INT",
@@ -79,7 +84,13 @@ def main() -> int:
         key, val = kv.split("=", 1)
         hp.hp_set_option(key, int(val))
 
+    from dataclasses import replace
     w = wl.CONFIGS[args.workload]()
+    if args.seq_shard:
+        w = replace(w, dst=replace(w.dst, tp_mode=wl.TP_SEQ_SHARD))
+    if args.dtype == "f32":
+        w = replace(w, maps=[replace(m, dtype=wl.DT_F32) for m in w.maps])
+    tdtype = torch.float32 if args.dtype == "f32" else torch.bfloat16
     maps = w.maps
     H = maps[0].hidden
     log(f"[bench] workload {w.name}: {len(maps)} microbatch(es), hidden {H}")
@@ -95,17 +106,17 @@ def main() -> int:
     sets = []
     for i, p in enumerate(plans):
         rows = p.src_rows()
-        src = [wl.random_bf16((r, H), w.seed * 100 + i * 7 + k, dev) for k, r in enumerate(rows)]
-        dst = [wl.random_bf16((p.info.dst_rows_per_buf, H), w.seed * 100 + 50 + j, dev)
+        src = [wl.random_bf16((r, H), w.seed * 100 + i * 7 + k, dev).to(tdtype) for k, r in enumerate(rows)]
+        dst = [wl.random_bf16((p.info.dst_rows_per_buf, H), w.seed * 100 + 50 + j, dev).to(tdtype)
                for j in range(p.info.n_dst_bufs)]
-        grad = [wl.random_bf16((p.info.dst_rows_per_buf, H), w.seed * 100 + 90 + j, dev)
+        grad = [wl.random_bf16((p.info.dst_rows_per_buf, H), w.seed * 100 + 90 + j, dev).to(tdtype)
                 for j in range(p.info.n_dst_bufs)]
-        sgrad = [torch.zeros((r, H), dtype=torch.bfloat16, device=dev) for r in rows]
+        sgrad = [torch.zeros((r, H), dtype=torch.float32 if args.accumulate else tdtype, device=dev) for r in rows]
         ps, pd = p.pointer_arrays(src, dst)
-        pgs, pgd = p.pointer_arrays(sgrad, grad)
+        pgs, pgd = p.pointer_arrays_accum(sgrad, grad) if args.accumulate else p.pointer_arrays(sgrad, grad)
         sets.append(dict(plan=p, src=src, dst=dst, grad=grad, sgrad=sgrad, ps=ps, pd=pd, pgs=pgs, pgd=pgd))
     fwd_bytes = sum(p.info.fwd_bytes for p in plans)
-    bwd_bytes = sum(p.info.bwd_bytes for p in plans)
+    bwd_bytes = sum(p.info.bwd_accum_bytes if args.accumulate else p.info.bwd_bytes for p in plans)
     boundary = sum(p.info.boundary_bytes for p in plans)
     log(f"[bench] boundary {boundary / 1e6:.1f} MB, fwd {fwd_bytes / 1e9:.3f} GB, bwd {bwd_bytes / 1e9:.3f} GB, "
         f"{sum(p.info.n_tiles for p in plans)} tiles, plan build {plan_ms:.2f} ms")
@@ -117,44 +128,65 @@ def main() -> int:
     tune_ms = None
     if not args.no_tune:
         t0 = time.perf_counter()
-        for s in sets:
+        s = sets[0]                      # plans of one workload share their grids: tune one, copy its shapes
+        if args.accumulate:              # the accumulating backward runs with the backward launch shape
+            tmp = [torch.zeros((r, H), dtype=tdtype, device=dev) for r in s["plan"].src_rows()]
+            s["plan"].tune(s["src"], s["dst"], s["grad"], tmp, stream)
+            del tmp
+        else:
             s["plan"].tune(s["src"], s["dst"], s["grad"], s["sgrad"], stream)
-        tune_ms = (time.perf_counter() - t0) * 1e3 / len(sets)
+        for other in sets[1:]:
+            for d in (0, 1):
+                other["plan"].set_launch(d, **s["plan"].get_launch(d))
+        tune_ms = (time.perf_counter() - t0) * 1e3
     shapes = {"fwd": sets[0]["plan"].get_launch(0), "bwd": sets[0]["plan"].get_launch(1)}
-    log(f"[bench] launch shapes: fwd {shapes['fwd']}  bwd {shapes['bwd']}  (tune {tune_ms} ms per plan)")
+    log(f"[bench] launch shapes: fwd {shapes['fwd']}  bwd {shapes['bwd']}  (tune {tune_ms} ms)")
 
     def step():
         for s in sets:
             s["plan"].forward_raw(s["ps"], s["pd"], stream)
         for s in sets:
-            s["plan"].backward_raw(s["pgd"], s["pgs"], stream)
+            if args.accumulate:
+                s["plan"].backward_accumulate_raw(s["pgd"], s["pgs"], stream)
+            else:
+                s["plan"].backward_raw(s["pgd"], s["pgs"], stream)
 
     for _ in range(args.warmup):
         step()
     stream.synchronize()
     torch.cuda.synchronize()
-    # Every launch in the timed region carries its own HIP event pair, stamped by
-    # the dispatch itself on the stream it runs on (no marker packets are added).
-    hp.hp_profile_enable(2 * n_launch * args.steps)
+    # Timed region: EXACTLY `steps` steps between two synchronisations -> `value`.
     t0 = time.perf_counter()
     for _ in range(args.steps):
         step()
     stream.synchronize()
     torch.cuda.synchronize()
     total_s = time.perf_counter() - t0
+    # The same `steps` steps again, now with a HIP event pair attached to every
+    # launch (stamped by the dispatch itself on the stream it runs on) -> kernel
+    # durations for the roofline.  Kept out of the region above because the
+    # runtime handles event-carrying dispatches one by one, which costs tens of
+    # microseconds per launch when a step is many short launches.
+    hp.hp_profile_enable(2 * n_launch * args.steps)
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    stream.synchronize()
+    torch.cuda.synchronize()
+    total_events_s = time.perf_counter() - t0
     launches = hp.hp_profile_read(2 * n_launch * args.steps)
     hp.hp_profile_enable(0)
     assert len(launches) == 2 * n_launch * args.steps
     per_step = [launches[i * 2 * n_launch:(i + 1) * 2 * n_launch] for i in range(args.steps)]
     fwd_ms = [sum(ms for kind, ms in st if kind == 0) for st in per_step]     # kernel time per step
-    bwd_ms = [sum(ms for kind, ms in st if kind == 1) for st in per_step]
+    bwd_ms = [sum(ms for kind, ms in st if kind != 0) for st in per_step]
     ms_per_step = total_s * 1e3 / args.steps
     value = (fwd_bytes + bwd_bytes) / (total_s / args.steps) / 1e9
     f_avg, b_avg = statistics.fmean(fwd_ms), statistics.fmean(bwd_ms)
     f_med, b_med = statistics.median(fwd_ms), statistics.median(bwd_ms)
     log(f"[bench] kernel time per step: fwd median {f_med:.4f} ms ({fwd_bytes / f_med / 1e6:.0f} GB/s), "
         f"bwd median {b_med:.4f} ms ({bwd_bytes / b_med / 1e6:.0f} GB/s); wall {ms_per_step:.4f} ms/step "
-        f"({value:.0f} GB/s)")
+        f"({value:.0f} GB/s); wall with per-launch events {total_events_s * 1e3 / args.steps:.4f} ms/step")
 
     # ---- plain device copy of the same byte count: practical ceiling ----
     n_copy = (fwd_bytes // 2) // 2
@@ -177,7 +209,7 @@ def main() -> int:
     p0i = sets[0]["plan"].info
     arr = max(int(min(boundary, 1 << 30)) // 4096 * 4096, 1 << 20)
     ceil_f, shape_f = hp.hp_probe_stream(1, min(p0i.dst_copies, 8), arr)
-    ceil_b, shape_b = hp.hp_probe_stream(min(p0i.dst_copies, 8), min(p0i.src_copies, 8), arr)
+    ceil_b, shape_b = hp.hp_probe_stream(min(p0i.dst_copies, 8), min(p0i.src_copies, 8), arr)   # (overwriting backward)
     log(f"[bench] pattern ceilings: 1R:{p0i.dst_copies}W {ceil_f:.0f} GB/s {shape_f}; "
         f"{p0i.dst_copies}R:{p0i.src_copies}W {ceil_b:.0f} GB/s {shape_b}")
 
@@ -198,7 +230,9 @@ def main() -> int:
 
     # ---- the CPU oracle on the same workload, host cores of this machine ----
     cpu_baseline = None
-    if not args.no_cpu_baseline:
+    if not args.no_cpu_baseline and (args.accumulate or args.dtype != "bf16"):
+        log("[bench] cpu_baseline is only timed for the bf16 overwriting backward; skipped")
+    elif not args.no_cpu_baseline:
         from oracle import oracle
         import numpy as np
         log("[bench] timing the CPU oracle on the same workload (first microbatch) ...")
@@ -238,11 +272,13 @@ def main() -> int:
         "metric": "boundary fwd+bwd effective HBM GB/s and % of MI355X HBM peak, 1 GPU",
         "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16 (backward accumulates in f32)", "data": "synthetic",
+        "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
         "config": {"workload": w.name, "src": f"tp{w.src.tp}dp{w.src.dp}",
                    "dst": f"tp{w.dst.tp}cp{w.dst.cp}dp{w.dst.dp}",
                    "batch": maps[0].batch, "seq": maps[0].seq, "hidden": H, "microbatches": len(maps),
-                   "launches_per_direction": n_launch, "launch_shapes": shapes, "tuned": not args.no_tune,
+                   "tp_mode": "seq_shard" if args.seq_shard else "replicate",
+                   "backward": "accumulate_f32" if args.accumulate else "overwrite",
+                   "accumulate_dtype": "f32", "launches_per_direction": n_launch, "launch_shapes": shapes, "tuned": not args.no_tune,
                    "image_rows": int(sum(m.n_rows for m in maps)), "boundary_bytes": boundary,
                    },
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
@@ -250,6 +286,7 @@ def main() -> int:
                     "GBps": fwd_bytes / f_med / 1e6, "pct_of_hbm_peak": fwd_bytes / f_med / 1e6 / HBM_PEAK_GBPS * 100},
         "backward": {"bytes": bwd_bytes, "median_ms": b_med, "min_ms": min(bwd_ms), "max_ms": max(bwd_ms),
                      "GBps": bwd_bytes / b_med / 1e6, "pct_of_hbm_peak": bwd_bytes / b_med / 1e6 / HBM_PEAK_GBPS * 100},
+        "ms_per_step_with_kernel_events": total_events_s * 1e3 / args.steps,
         "plan_build_ms": plan_ms, "plan_tune_ms": tune_ms,
         "device_copy_GBps": copy_gbps,
         "pattern_ceiling": {"forward_GBps": ceil_f, "backward_GBps": ceil_b, "array_bytes": arr,

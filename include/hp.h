@@ -140,6 +140,9 @@ typedef struct hp_plan_info {
     int32_t on_device;         /* 1 if device tables exist                                    */
     int32_t device;            /* HIP device ordinal of the tables, -1 if none                */
     int32_t n_maps;            /* microbatches folded into the plan (1 unless batched)        */
+    int32_t elem_bytes;        /* 2 for HP_BF16, 4 for HP_F32                                 */
+    int64_t bwd_accum_bytes;   /* algorithmic traffic of hp_backward_accumulate: dst_copies *
+                                  boundary read + src_copies * N * hidden * 4 read and written */
 } hp_plan_info_t;
 
 /* A maximal run of image-token rows that is contiguous in the source buffer and

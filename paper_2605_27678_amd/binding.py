@@ -50,7 +50,8 @@ class hp_plan_info_t(C.Structure):
                 ("n_rows", C.c_int64), ("row_bytes", C.c_int64), ("dst_rows_per_buf", C.c_int64),
                 ("boundary_bytes", C.c_int64), ("fwd_bytes", C.c_int64), ("bwd_bytes", C.c_int64),
                 ("n_segments", C.c_int32), ("n_tiles", C.c_int32),
-                ("on_device", C.c_int32), ("device", C.c_int32), ("n_maps", C.c_int32)]
+                ("on_device", C.c_int32), ("device", C.c_int32), ("n_maps", C.c_int32),
+                ("elem_bytes", C.c_int32), ("bwd_accum_bytes", C.c_int64)]
 
 
 class hp_segment_t(C.Structure):
@@ -209,7 +210,7 @@ class Plan:
         del keep
         self.info = hp_plan_info_t()
         _check(L.hp_plan_query(self._h, C.byref(self.info)), "hp_plan_query")
-        self.elem_bytes = self.info.row_bytes // self.hidden
+        self.elem_bytes = self.info.elem_bytes
 
     def get_launch(self, direction: int) -> dict:
         out = hp_launch_t()
@@ -291,6 +292,12 @@ class Plan:
 
     def backward_raw(self, pd, ps, stream=None) -> None:
         _check(_lib().hp_backward(self._h, pd, ps, _stream_handle(stream)), "hp_backward")
+
+    def backward_accumulate_raw(self, pd, ps, stream=None) -> None:
+        _check(_lib().hp_backward_accumulate(self._h, pd, ps, _stream_handle(stream)), "hp_backward_accumulate")
+
+    def pointer_arrays_accum(self, src_accum_bufs: Sequence, dst_grad_bufs: Sequence):
+        return self._src_dst(src_accum_bufs, dst_grad_bufs, src_esize=4)
 
     def close(self) -> None:
         if self._h:

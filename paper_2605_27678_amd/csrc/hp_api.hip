@@ -789,6 +789,9 @@ int hp_plan_query(const hp_plan_t *p, hp_plan_info_t *info) {
     o.on_device = (p->d_segs != nullptr || (p->device >= 0 && p->segments.empty())) ? 1 : 0;
     o.device = p->device;
     o.n_maps = p->n_maps;
+    o.elem_bytes = p->elem_bytes;
+    o.bwd_accum_bytes = (int64_t)p->dst_copies * o.boundary_bytes +
+                        (int64_t)p->src_copies * 2 * p->n_rows * p->hidden * 4;
     *info = o;
     return HP_OK;
 }
