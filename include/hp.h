@@ -43,12 +43,16 @@
  *     subnormals kept, then one rounding to bf16.  (The paper's own stack
  *     returns the leader's copy without a reduction.)
  *
- * Threading / ownership: a plan is immutable after creation and may be used
- * from several host threads and streams at once.  The caller owns every
- * activation and gradient buffer and the stream; the plan owns only its device
- * tables.  hp_forward / hp_backward enqueue work on the caller's stream and
- * return without synchronising; they allocate nothing.  Buffers must stay valid
- * until the stream has passed the call.
+ * Threading / ownership: apart from its launch shapes (hp_plan_set_launch,
+ * hp_plan_tune) a plan is immutable after creation and may be used from several
+ * host threads and streams at once.  The caller owns every activation and
+ * gradient buffer and the stream; the plan owns only its device tables (a few
+ * KB).  hp_forward / hp_backward / hp_backward_accumulate enqueue one kernel on
+ * the caller's stream and return without synchronising; they allocate nothing
+ * and use no scratch memory.  Buffers must stay valid until the stream has
+ * passed the call.  The library performs no bounds checks on the caller's
+ * buffers: each must hold at least the rows hp_plan_src_rows /
+ * hp_plan_query report.
  *
  * Errors: every int-returning call returns HP_OK (0) or a negative HP_E* code;
  * nothing throws or aborts across this boundary and output arguments are left

@@ -432,8 +432,17 @@ struct LaunchCfg {
     EventPair ev;         // optional timing events for this dispatch
 };
 
-#define HP_LAUNCH(kernel, c, ...) \
-    hipExtLaunchKernelGGL(kernel, (c).grid, (c).block, (c).lds_bytes, (c).stream, (c).ev.start, (c).ev.stop, 0, __VA_ARGS__)
+// The plain launch is the normal path (it can also be recorded into a HIP graph
+// by a capturing caller); the extended launch is used only when this dispatch
+// carries timing events.
+#define HP_LAUNCH(kernel, c, ...)                                                                    \
+    do {                                                                                             \
+        if ((c).ev.start)                                                                            \
+            hipExtLaunchKernelGGL(kernel, (c).grid, (c).block, (c).lds_bytes, (c).stream,            \
+                                  (c).ev.start, (c).ev.stop, 0, __VA_ARGS__);                        \
+        else                                                                                         \
+            hipLaunchKernelGGL(kernel, (c).grid, (c).block, (c).lds_bytes, (c).stream, __VA_ARGS__); \
+    } while (0)
 
 // Both kernels run fastest well below full occupancy: with every wave slot busy
 // the window of addresses in flight is wide and HBM efficiency drops.  The cap

@@ -421,3 +421,39 @@ def test_two_edges_join_in_one_sequence():
         prob.backward_bf16(hg, want)
         for a, b in zip(got, want):
             assert np.array_equal(_to_host_bits(a), b)
+
+
+def test_calls_can_be_captured_in_a_hip_graph():
+    """hp_forward + hp_backward recorded into a graph by a capturing caller and
+    replayed several times, with eager work and synchronisations between the
+    replays; every replay must reproduce the eager result bit for bit."""
+    w = wl.scaled(wl.long_context(), 384)
+    tm = w.maps[0]
+    plan = hp.hp_plan_create(w.src, w.dst, tm)
+    rows, drows = plan.src_rows(), plan.info.dst_rows_per_buf
+    src = [wl.random_bf16((r, 384), 3 + i, "cuda") for i, r in enumerate(rows)]
+    pre = [wl.random_bf16((drows, 384), 40 + j, "cuda") for j in range(32)]
+    dst = [t.clone() for t in pre]
+    sg = [torch.zeros_like(t) for t in src]
+    # eager reference
+    hp.hp_forward(plan, src, dst)
+    hp.hp_backward(plan, dst, sg)
+    torch.cuda.synchronize()
+    want_dst = [t.clone() for t in dst]
+    want_sg = [t.clone() for t in sg]
+    st = torch.cuda.Stream()
+    g = torch.cuda.CUDAGraph()
+    st.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.graph(g, stream=st):
+        hp.hp_forward(plan, src, dst, torch.cuda.current_stream())
+        hp.hp_backward(plan, dst, sg, torch.cuda.current_stream())
+    for rep in range(3):
+        for t, p0 in zip(dst, pre):
+            t.copy_(p0)                        # eager work between replays: restore the prefill,
+        for t in sg:
+            t.fill_(float(rep))                # scribble on the outputs
+        torch.cuda.synchronize()
+        g.replay()
+        torch.cuda.synchronize()
+        assert all(torch.equal(a.view(torch.int16), b.view(torch.int16)) for a, b in zip(dst, want_dst)), rep
+        assert all(torch.equal(a.view(torch.int16), b.view(torch.int16)) for a, b in zip(sg, want_sg)), rep
