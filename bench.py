@@ -188,6 +188,15 @@ def main() -> int:
         f"bwd median {b_med:.4f} ms ({bwd_bytes / b_med / 1e6:.0f} GB/s); wall {ms_per_step:.4f} ms/step "
         f"({value:.0f} GB/s); wall with per-launch events {total_events_s * 1e3 / args.steps:.4f} ms/step")
 
+    # ---- rebuilding the plan at step rate (token maps change every step): warm create + destroy ----
+    t0 = time.perf_counter()
+    for _ in range(20):
+        q = hp.hp_plan_create_batched(w.src, w.dst, maps) if len(plans) == 1 and len(maps) > 1 \
+            else hp.hp_plan_create(w.src, w.dst, maps[0])
+        q.close()
+    plan_rebuild_ms = (time.perf_counter() - t0) * 1e3 / 20
+    log(f"[bench] plan create+destroy, warm: {plan_rebuild_ms:.3f} ms")
+
     # ---- plain device copy of the same byte count: practical ceiling ----
     n_copy = (fwd_bytes // 2) // 2
     a = torch.empty(n_copy, dtype=torch.bfloat16, device=dev)
@@ -287,7 +296,7 @@ def main() -> int:
         "backward": {"bytes": bwd_bytes, "median_ms": b_med, "min_ms": min(bwd_ms), "max_ms": max(bwd_ms),
                      "GBps": bwd_bytes / b_med / 1e6, "pct_of_hbm_peak": bwd_bytes / b_med / 1e6 / HBM_PEAK_GBPS * 100},
         "ms_per_step_with_kernel_events": total_events_s * 1e3 / args.steps,
-        "plan_build_ms": plan_ms, "plan_tune_ms": tune_ms,
+        "plan_build_ms": plan_ms, "plan_rebuild_ms": plan_rebuild_ms, "plan_tune_ms": tune_ms,
         "device_copy_GBps": copy_gbps,
         "pattern_ceiling": {"forward_GBps": ceil_f, "backward_GBps": ceil_b, "array_bytes": arr,
                             "forward_shape": shape_f, "backward_shape": shape_b},

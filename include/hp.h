@@ -189,9 +189,15 @@ int hp_plan_create_batched(const hp_layout_t *src, const hp_layout_t *dst,
                            const hp_token_map_t *maps, int32_t n_maps,
                            int32_t host_only, hp_plan_t **out);
 
-/* Frees host and device tables.  NULL is allowed.  The caller must have
+/* Frees the host tables and hands the device block (a few KB) back to a small
+ * per-process cache from which later hp_plan_create calls on the same device
+ * are served, so that plans can be rebuilt at training-step rate without a
+ * hipMalloc / hipFree pair each time.  NULL is allowed.  The caller must have
  * synchronised every stream that still uses the plan. */
 void hp_plan_destroy(hp_plan_t *plan);
+
+/* hipFree()s every cached device block (at most 64 blocks of a few KB). */
+void hp_release_cached_memory(void);
 
 int hp_plan_query(const hp_plan_t *plan, hp_plan_info_t *info);
 
@@ -272,9 +278,15 @@ int hp_plan_set_launch(hp_plan_t *plan, int32_t direction, const hp_launch_t *in
  * compute exactly what hp_forward / hp_backward compute, so the buffers end up
  * as after one such call.  SYNCHRONOUS: waits on `stream` repeatedly, takes
  * tens of milliseconds, creates and destroys two HIP events, and must not run
- * concurrently with other calls that use the same plan. */
+ * concurrently with other calls that use the same plan.
+ * The winning shapes are also remembered per problem class (dtype, row size,
+ * TP_dst copies, TP_src copies, device): plans of the same class created later
+ * by hp_plan_create / hp_plan_create_batched start from them instead of the
+ * process-wide defaults, so a caller that rebuilds its plan every step tunes
+ * once.  hp_forget_tuned_shapes drops what was remembered. */
 int hp_plan_tune(hp_plan_t *plan, const void *const *src_bufs, void *const *dst_bufs,
                  const void *const *dst_grad_bufs, void *const *src_grad_bufs, void *stream);
+void hp_forget_tuned_shapes(void);
 
 /* Process-wide defaults copied into every plan created afterwards (integers).
  * Keys: "tile_bytes_fwd", "tile_bytes_bwd", "block_threads_fwd",

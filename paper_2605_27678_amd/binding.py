@@ -65,6 +65,7 @@ class hp_launch_t(C.Structure):
 
 
 EXPORTS = ["hp_plan_create", "hp_plan_create_host", "hp_plan_create_batched", "hp_plan_destroy",
+           "hp_release_cached_memory", "hp_forget_tuned_shapes",
            "hp_plan_query", "hp_plan_src_rows", "hp_plan_segments", "hp_plan_get_launch",
            "hp_plan_set_launch", "hp_plan_tune", "hp_forward", "hp_backward", "hp_backward_accumulate",
            "hp_set_option", "hp_get_option", "hp_probe_stream", "hp_profile_enable", "hp_profile_read",
@@ -94,6 +95,8 @@ def _lib():
     L.hp_plan_tune.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), vp]
     L.hp_plan_destroy.argtypes = [vp]
     L.hp_plan_destroy.restype = None
+    L.hp_release_cached_memory.restype = None
+    L.hp_forget_tuned_shapes.restype = None
     L.hp_plan_query.argtypes = [vp, C.POINTER(hp_plan_info_t)]
     L.hp_plan_src_rows.argtypes = [vp, C.POINTER(i64), i32]
     L.hp_plan_segments.argtypes = [vp, C.POINTER(hp_segment_t), i32]
@@ -172,6 +175,14 @@ def hp_profile_read(cap: int):
     kinds = (C.c_int32 * max(cap, 1))()
     n = _check(_lib().hp_profile_read(ms, kinds, cap), "hp_profile_read")
     return [(int(kinds[i]), float(ms[i])) for i in range(min(n, cap))]
+
+
+def hp_forget_tuned_shapes() -> None:
+    _lib().hp_forget_tuned_shapes()
+
+
+def hp_release_cached_memory() -> None:
+    _lib().hp_release_cached_memory()
 
 
 def hp_version() -> str:

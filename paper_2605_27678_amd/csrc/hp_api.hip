@@ -607,6 +607,101 @@ bool launch_ok(const hp::Launch &L) {
            L.nontemporal <= 3;
 }
 
+// Device blocks for plan tables are recycled: token maps change every training
+// step, so plans are created and destroyed at step rate, and a hipMalloc +
+// hipFree pair costs far more than building the tables.  Blocks come in 4 KiB
+// size classes; a destroyed plan's block waits here for the next plan on the
+// same device.
+struct TablePool {
+    struct Block { void *p; size_t bytes; int device; };
+    std::mutex mu;
+    std::vector<Block> free_blocks;
+    static constexpr size_t kMaxCached = 64;
+
+    void *get(size_t need, int device, size_t *got, int *rc) {
+        need = (need + 4095) / 4096 * 4096;
+        {
+            std::lock_guard<std::mutex> lk(mu);
+            size_t best = free_blocks.size();
+            for (size_t i = 0; i < free_blocks.size(); ++i)
+                if (free_blocks[i].device == device && free_blocks[i].bytes >= need &&
+                    (best == free_blocks.size() || free_blocks[i].bytes < free_blocks[best].bytes))
+                    best = i;
+            if (best != free_blocks.size()) {
+                Block b = free_blocks[best];
+                free_blocks.erase(free_blocks.begin() + best);
+                *got = b.bytes;
+                return b.p;
+            }
+        }
+        void *p = nullptr;
+        hipError_t e = hipMalloc(&p, need);
+        if (e == hipErrorOutOfMemory) { g_last_hip_error = (int)e; *rc = HP_ENOMEM; return nullptr; }
+        if (hip_failed(e)) { *rc = HP_EHIP; return nullptr; }
+        *got = need;
+        return p;
+    }
+    void put(void *p, size_t bytes, int device) {
+        if (!p) return;
+        {
+            std::lock_guard<std::mutex> lk(mu);
+            if (free_blocks.size() < kMaxCached) {
+                free_blocks.push_back(Block{p, bytes, device});
+                return;
+            }
+        }
+        (void)hipFree(p);
+    }
+    void release_all() {
+        std::vector<Block> blocks;
+        {
+            std::lock_guard<std::mutex> lk(mu);
+            blocks.swap(free_blocks);
+        }
+        for (const Block &b : blocks) (void)hipFree(b.p);
+    }
+} g_pool;
+
+// Launch shapes found by hp_plan_tune are remembered per problem class (dtype,
+// row size, replica counts, device) and seed later plans of the same class, so a
+// caller that rebuilds its plan every step tunes once.
+struct ShapeCache {
+    struct Entry { int dtype; int64_t row_bytes; int dst_copies, src_copies, device; hp::Launch fwd, bwd; bool has_fwd, has_bwd; };
+    std::mutex mu;
+    std::vector<Entry> entries;
+
+    Entry *find(const hp_plan *p) {
+        for (Entry &e : entries)
+            if (e.dtype == p->dtype && e.row_bytes == p->row_bytes && e.dst_copies == p->dst_copies &&
+                e.src_copies == p->src_copies && e.device == p->device)
+                return &e;
+        return nullptr;
+    }
+    void remember(const hp_plan *p, bool fwd, bool bwd) {
+        std::lock_guard<std::mutex> lk(mu);
+        Entry *e = find(p);
+        if (!e) {
+            if (entries.size() >= 256) entries.erase(entries.begin());
+            entries.push_back(Entry{p->dtype, p->row_bytes, p->dst_copies, p->src_copies, p->device, p->fwd, p->bwd,
+                                    false, false});
+            e = &entries.back();
+        }
+        if (fwd) { e->fwd = p->fwd; e->has_fwd = true; }
+        if (bwd) { e->bwd = p->bwd; e->has_bwd = true; }
+    }
+    void apply(hp_plan *p) {
+        std::lock_guard<std::mutex> lk(mu);
+        if (const Entry *e = find(p)) {
+            if (e->has_fwd) p->fwd = e->fwd;
+            if (e->has_bwd) p->bwd = e->bwd;
+        }
+    }
+    void clear() {
+        std::lock_guard<std::mutex> lk(mu);
+        entries.clear();
+    }
+} g_shapes;
+
 int create_common(const hp_layout_t *src, const hp_layout_t *dst, const hp_token_map_t *maps,
                   int32_t n_maps, bool upload, hp_plan_t **out) {
     if (!out) return HP_EINVAL;
@@ -622,22 +717,28 @@ int create_common(const hp_layout_t *src, const hp_layout_t *dst, const hp_token
     }
     if (rc == HP_OK && upload) {
         if (hip_failed(hipGetDevice(&p->device))) rc = HP_EHIP;
+        if (rc == HP_OK) g_shapes.apply(p);
         if (rc == HP_OK && !p->segments.empty()) {
+            // descriptors and prefix arrays go up in one copy
             const size_t seg_bytes = p->dsegs.size() * sizeof(hp::Seg);
             const size_t first_bytes = p->first_tile.size() * sizeof(uint32_t);
-            hipError_t e = hipMalloc((void **)&p->d_segs, seg_bytes + first_bytes);
-            if (e == hipErrorOutOfMemory) { g_last_hip_error = (int)e; rc = HP_ENOMEM; }
-            else if (hip_failed(e)) rc = HP_EHIP;
-            if (rc == HP_OK) {
-                p->d_first = (uint32_t *)((char *)p->d_segs + seg_bytes);
-                if (hip_failed(hipMemcpy(p->d_segs, p->dsegs.data(), seg_bytes, hipMemcpyHostToDevice)) ||
-                    hip_failed(hipMemcpy(p->d_first, p->first_tile.data(), first_bytes, hipMemcpyHostToDevice)))
-                    rc = HP_EHIP;
+            try {
+                std::vector<char> staging(seg_bytes + first_bytes);
+                std::memcpy(staging.data(), p->dsegs.data(), seg_bytes);
+                std::memcpy(staging.data() + seg_bytes, p->first_tile.data(), first_bytes);
+                p->d_segs = (hp::Seg *)g_pool.get(staging.size(), p->device, &p->d_bytes, &rc);
+                if (rc == HP_OK) {
+                    p->d_first = (uint32_t *)((char *)p->d_segs + seg_bytes);
+                    if (hip_failed(hipMemcpy(p->d_segs, staging.data(), staging.size(), hipMemcpyHostToDevice)))
+                        rc = HP_EHIP;
+                }
+            } catch (const std::bad_alloc &) {
+                rc = HP_ENOMEM;
             }
         }
     }
     if (rc != HP_OK) {
-        if (p->d_segs) (void)hipFree(p->d_segs);
+        g_pool.put(p->d_segs, p->d_bytes, p->device);
         delete p;
         return rc;
     }
@@ -775,9 +876,13 @@ int hp_plan_create_batched(const hp_layout_t *src, const hp_layout_t *dst, const
 
 void hp_plan_destroy(hp_plan_t *plan) {
     if (!plan) return;
-    if (plan->d_segs) (void)hipFree(plan->d_segs);
+    g_pool.put(plan->d_segs, plan->d_bytes, plan->device);
     delete plan;
 }
+
+void hp_release_cached_memory(void) { g_pool.release_all(); }
+
+void hp_forget_tuned_shapes(void) { g_shapes.clear(); }
 
 int hp_plan_query(const hp_plan_t *p, hp_plan_info_t *info) {
     if (!p || !info) return HP_EINVAL;
@@ -873,10 +978,12 @@ int hp_plan_tune(hp_plan_t *p, const void *const *src_bufs, void *const *dst_buf
     if (src_bufs) {
         rc = prepare(p, kForward, src_bufs, (const void *const *)dst_bufs, &bt, &width);
         if (rc == HP_OK) rc = tune_direction(p, kForward, bt, width, (hipStream_t)stream);
+        if (rc == HP_OK) g_shapes.remember(p, true, false);
     }
     if (rc == HP_OK && dst_grad_bufs) {
         rc = prepare(p, kBackward, (const void *const *)src_grad_bufs, dst_grad_bufs, &bt, &width);
         if (rc == HP_OK) rc = tune_direction(p, kBackward, bt, width, (hipStream_t)stream);
+        if (rc == HP_OK) g_shapes.remember(p, false, true);
     }
     return rc;
 }

@@ -68,6 +68,7 @@ struct hp_plan {
     // device side
     hp::Seg *d_segs = nullptr;
     uint32_t *d_first = nullptr;
+    size_t d_bytes = 0;                   // size of the device block behind d_segs
     int device = -1;
 
     uint32_t n_tiles(int variant) const {

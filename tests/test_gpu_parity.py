@@ -25,6 +25,7 @@ def _default_options():
     yield
     for k, v in saved.items():
         hp.hp_set_option(k, v)
+    hp.hp_forget_tuned_shapes()
 
 
 def test_tiny_config():
@@ -329,6 +330,14 @@ def test_tune_keeps_results_exact_and_picks_a_valid_shape():
     st.synchronize()
     assert all(torch.equal(a, b) for a, b in zip(sg, sg2))
     hp.hp_plan_tune(plan, src, dst, None, None, st)          # one direction only
+    # a later plan of the same problem class starts from the tuned shapes
+    tuned = (plan.get_launch(0), plan.get_launch(1))
+    other = hp.hp_plan_create(w.src, w.dst, wl.scaled(wl.long_context(n_images=5), 1024).maps[0])
+    assert (other.get_launch(0), other.get_launch(1)) == tuned
+    hp.hp_forget_tuned_shapes()
+    fresh = hp.hp_plan_create(w.src, w.dst, tm)
+    assert fresh.get_launch(0)["tile_bytes"] == hp.hp_get_option("tile_bytes_fwd")
+    assert fresh.get_launch(0)["waves_per_cu"] == hp.hp_get_option("waves_per_cu_fwd")
 
 
 def test_stream_probe_reports_a_rate():
@@ -457,3 +466,27 @@ def test_calls_can_be_captured_in_a_hip_graph():
         torch.cuda.synchronize()
         assert all(torch.equal(a.view(torch.int16), b.view(torch.int16)) for a, b in zip(dst, want_dst)), rep
         assert all(torch.equal(a.view(torch.int16), b.view(torch.int16)) for a, b in zip(sg, want_sg)), rep
+
+
+def test_plans_rebuilt_every_step_reuse_device_blocks():
+    """Token maps change every step: create, use and destroy 40 plans in a row
+    (device table blocks are recycled) and check each result."""
+    rng = np.random.default_rng(99)
+    src, dst = wl.Grid(dp=4), wl.Grid(tp=2, cp=2, cp_split=wl.CP_ZIGZAG)
+    H = 128
+    for step in range(40):
+        lens = [int(x) for x in rng.integers(1, 40, size=int(rng.integers(1, 9)))]
+        tm = wl.token_map_from_lens(rng, 1, 512, H, [lens])
+        plan = hp.hp_plan_create(src, dst, tm)
+        prob = oracle.Problem(src, dst, tm)
+        xs = [wl.random_bf16((r, H), step * 10 + i) for i, r in enumerate(plan.src_rows())]
+        pre = [wl.random_bf16((plan.info.dst_rows_per_buf, H), step * 10 + 5 + j) for j in range(4)]
+        g_dst = [t.cuda() for t in pre]
+        hp.hp_forward(plan, [t.cuda() if t.numel() else None for t in xs], g_dst)
+        torch.cuda.synchronize()
+        plan.close()
+        want = [_to_host_bits(t).copy() for t in pre]
+        prob.forward([_to_host_bits(t) for t in xs], want)
+        for j in range(4):
+            assert np.array_equal(_to_host_bits(g_dst[j]), want[j]), (step, j)
+    hp.hp_release_cached_memory()
