@@ -129,17 +129,18 @@ def main() -> int:
     if not args.no_tune:
         t0 = time.perf_counter()
         s = sets[0]                      # plans of one workload share their grids: tune one, copy its shapes
-        if args.accumulate:              # the accumulating backward runs with the backward launch shape
-            tmp = [torch.zeros((r, H), dtype=tdtype, device=dev) for r in s["plan"].src_rows()]
-            s["plan"].tune(s["src"], s["dst"], s["grad"], tmp, stream)
+        if args.accumulate:              # tune on scratch accumulators: every candidate launch adds into them
+            tmp = [torch.zeros((r, H), dtype=torch.float32, device=dev) for r in s["plan"].src_rows()]
+            s["plan"].tune(s["src"], s["dst"], None, None, stream)
+            s["plan"].tune_accumulate(s["grad"], tmp, stream)
             del tmp
         else:
             s["plan"].tune(s["src"], s["dst"], s["grad"], s["sgrad"], stream)
         for other in sets[1:]:
-            for d in (0, 1):
+            for d in (0, 1, 2):
                 other["plan"].set_launch(d, **s["plan"].get_launch(d))
         tune_ms = (time.perf_counter() - t0) * 1e3
-    shapes = {"fwd": sets[0]["plan"].get_launch(0), "bwd": sets[0]["plan"].get_launch(1)}
+    shapes = {"fwd": sets[0]["plan"].get_launch(0), "bwd": sets[0]["plan"].get_launch(2 if args.accumulate else 1)}
     log(f"[bench] launch shapes: fwd {shapes['fwd']}  bwd {shapes['bwd']}  (tune {tune_ms} ms)")
 
     def step():

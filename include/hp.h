@@ -254,12 +254,14 @@ int hp_backward(const hp_plan_t *plan, const void *const *dst_grad_bufs,
  *   src_accum_bufs: HOST array of n_src_bufs DEVICE pointers to binary32 arrays
  *                   [rows_i, hidden], read and written; 4-byte aligned (16-byte
  *                   alignment and hidden % 4 == 0 select the vector path).
- * Uses the plan's hp_backward launch shape. */
+ * Has its own launch shape (direction 2). */
 int hp_backward_accumulate(const hp_plan_t *plan, const void *const *dst_grad_bufs,
                            void *const *src_accum_bufs, void *stream);
 
 /* Launch shape of one direction of a plan (direction 0 = hp_forward,
- * 1 = hp_backward).  A plan starts from the process-wide defaults below. */
+ * 1 = hp_backward, 2 = hp_backward_accumulate).  A plan starts from the
+ * process-wide defaults below (the accumulating backward from the backward
+ * defaults with tiles of at least 4 KiB). */
 typedef struct hp_launch {
     int32_t tile_bytes;      /* boundary bytes per workgroup: 1024 << k, k = 0..6              */
     int32_t block_threads;   /* workgroup size: multiple of 64 in [64, 1024]                   */
@@ -276,8 +278,11 @@ int hp_plan_set_launch(hp_plan_t *plan, int32_t direction, const hp_launch_t *in
  * narrow).  Arguments as for hp_forward and hp_backward; pass both pointers of
  * a direction as NULL to leave that direction alone.  The candidate launches
  * compute exactly what hp_forward / hp_backward compute, so the buffers end up
- * as after one such call.  SYNCHRONOUS: waits on `stream` repeatedly, takes
- * tens of milliseconds, creates and destroys two HIP events, and must not run
+ * as after one such call.  Candidates are timed as bursts of back-to-back
+ * launches, so that work a shape leaves behind at the end of a kernel (dirty
+ * lines still draining to HBM) is charged to it and not to the next kernel.
+ * SYNCHRONOUS: waits on `stream` repeatedly, takes
+ * tens of milliseconds, creates and destroys four HIP events, and must not run
  * concurrently with other calls that use the same plan.
  * The winning shapes are also remembered per problem class (dtype, row size,
  * TP_dst copies, TP_src copies, device): plans of the same class created later
@@ -287,6 +292,13 @@ int hp_plan_set_launch(hp_plan_t *plan, int32_t direction, const hp_launch_t *in
 int hp_plan_tune(hp_plan_t *plan, const void *const *src_bufs, void *const *dst_bufs,
                  const void *const *dst_grad_bufs, void *const *src_grad_bufs, void *stream);
 void hp_forget_tuned_shapes(void);
+
+/* The same search for hp_backward_accumulate (direction 2).  Every candidate
+ * launch ADDS the folded gradients to src_accum_bufs, an unspecified number of
+ * times in total: pass scratch accumulators of the right shape, not live ones.
+ * Otherwise as hp_plan_tune. */
+int hp_plan_tune_accumulate(hp_plan_t *plan, const void *const *dst_grad_bufs,
+                            void *const *src_accum_bufs, void *stream);
 
 /* Process-wide defaults copied into every plan created afterwards (integers).
  * Keys: "tile_bytes_fwd", "tile_bytes_bwd", "block_threads_fwd",

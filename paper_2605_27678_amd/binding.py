@@ -67,7 +67,7 @@ class hp_launch_t(C.Structure):
 EXPORTS = ["hp_plan_create", "hp_plan_create_host", "hp_plan_create_batched", "hp_plan_destroy",
            "hp_release_cached_memory", "hp_forget_tuned_shapes",
            "hp_plan_query", "hp_plan_src_rows", "hp_plan_segments", "hp_plan_get_launch",
-           "hp_plan_set_launch", "hp_plan_tune", "hp_forward", "hp_backward", "hp_backward_accumulate",
+           "hp_plan_set_launch", "hp_plan_tune", "hp_plan_tune_accumulate", "hp_forward", "hp_backward", "hp_backward_accumulate",
            "hp_set_option", "hp_get_option", "hp_probe_stream", "hp_profile_enable", "hp_profile_read",
            "hp_strerror", "hp_last_hip_error", "hp_version"]
 
@@ -93,6 +93,8 @@ def _lib():
     L.hp_plan_get_launch.argtypes = [vp, i32, C.POINTER(hp_launch_t)]
     L.hp_plan_set_launch.argtypes = [vp, i32, C.POINTER(hp_launch_t)]
     L.hp_plan_tune.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), vp]
+    L.hp_plan_tune_accumulate.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp]
+    L.hp_plan_tune_accumulate.restype = C.c_int
     L.hp_plan_destroy.argtypes = [vp]
     L.hp_plan_destroy.restype = None
     L.hp_release_cached_memory.restype = None
@@ -279,6 +281,11 @@ class Plan:
         ps = self._pointers(src_bufs, self.src_rows(), "src", src_esize)
         pd = self._pointers(dst_bufs, [self.info.dst_rows_per_buf] * len(dst_bufs), "dst")
         return ps, pd
+
+    def tune_accumulate(self, dst_grad_bufs, src_accum_scratch, stream=None) -> None:
+        """Launch-shape search for backward_accumulate; adds into src_accum_scratch many times."""
+        ps, pd = self._src_dst(src_accum_scratch, dst_grad_bufs, src_esize=4)
+        _check(_lib().hp_plan_tune_accumulate(self._h, pd, ps, _stream_handle(stream)), "hp_plan_tune_accumulate")
 
     def forward(self, src_bufs: Sequence, dst_bufs: Sequence, stream=None) -> None:
         ps, pd = self._src_dst(src_bufs, dst_bufs)

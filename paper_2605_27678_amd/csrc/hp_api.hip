@@ -502,7 +502,8 @@ void launch_backward_shape(int dtype, bool acc, int elems, int copies, const Lau
             else launch_backward_nrep<HP_F32, 1, false, NTL, NTS>(copies, c, bt, k);
         }
     } else if (acc) {
-        if (elems == 4) launch_backward_nrep<HP_BF16, 4, true, NTL, NTS>(copies, c, bt, k);
+        if (elems == 8) launch_backward_nrep<HP_BF16, 8, true, NTL, NTS>(copies, c, bt, k);
+        else if (elems == 4) launch_backward_nrep<HP_BF16, 4, true, NTL, NTS>(copies, c, bt, k);
         else launch_backward_nrep<HP_BF16, 1, true, NTL, NTS>(copies, c, bt, k);
     } else {
         if (elems == 8) launch_backward_nrep<HP_BF16, 8, false, NTL, NTS>(copies, c, bt, k);
@@ -586,7 +587,9 @@ int prepare(const hp_plan *p, Direction dir, const void *const *src, const void 
     }
     const uint64_t eb = (uint64_t)p->elem_bytes;
     if (dir == kBackwardAcc) {
-        if (((dst_bits & (4 * eb - 1)) | (src_bits & 15)) == 0) *lane = 4;
+        // bf16 gradients: 16-byte loads, two 16-byte accumulator chunks per lane
+        if (eb == 2 && ((dst_bits & 15) | (src_bits & 31)) == 0) *lane = 8;
+        else if (((dst_bits & (4 * eb - 1)) | (src_bits & 15)) == 0) *lane = 4;
         else if (((dst_bits & (eb - 1)) | (src_bits & 3)) == 0) *lane = 1;
         else return HP_EALIGN;
     } else {
@@ -666,7 +669,7 @@ struct TablePool {
 // row size, replica counts, device) and seed later plans of the same class, so a
 // caller that rebuilds its plan every step tunes once.
 struct ShapeCache {
-    struct Entry { int dtype; int64_t row_bytes; int dst_copies, src_copies, device; hp::Launch fwd, bwd; bool has_fwd, has_bwd; };
+    struct Entry { int dtype; int64_t row_bytes; int dst_copies, src_copies, device; hp::Launch fwd, bwd, acc; bool has_fwd, has_bwd, has_acc; };
     std::mutex mu;
     std::vector<Entry> entries;
 
@@ -677,23 +680,25 @@ struct ShapeCache {
                 return &e;
         return nullptr;
     }
-    void remember(const hp_plan *p, bool fwd, bool bwd) {
+    void remember(const hp_plan *p, bool fwd, bool bwd, bool acc = false) {
         std::lock_guard<std::mutex> lk(mu);
         Entry *e = find(p);
         if (!e) {
             if (entries.size() >= 256) entries.erase(entries.begin());
             entries.push_back(Entry{p->dtype, p->row_bytes, p->dst_copies, p->src_copies, p->device, p->fwd, p->bwd,
-                                    false, false});
+                                    p->acc, false, false, false});
             e = &entries.back();
         }
         if (fwd) { e->fwd = p->fwd; e->has_fwd = true; }
         if (bwd) { e->bwd = p->bwd; e->has_bwd = true; }
+        if (acc) { e->acc = p->acc; e->has_acc = true; }
     }
     void apply(hp_plan *p) {
         std::lock_guard<std::mutex> lk(mu);
         if (const Entry *e = find(p)) {
             if (e->has_fwd) p->fwd = e->fwd;
             if (e->has_bwd) p->bwd = e->bwd;
+            if (e->has_acc) p->acc = e->acc;
         }
     }
     void clear() {
@@ -763,36 +768,60 @@ const OptionDesc kOptions[] = {
     {"waves_per_cu_bwd", &hp::Options::waves_per_cu_bwd, 0, 32, 1, false},
 };
 
-// Times `reps` launches of one candidate (after one warm-up launch).  Returns
-// the minimum or the median kernel duration in milliseconds, or a negative
-// value on a HIP error.
-float time_candidate(const hp_plan *p, Direction dir, const hp::Launch &L, const BufTable &bt, int width,
-                     hipStream_t stream, EventPair ev, int reps, bool median) {
-    float t[16];
-    if (reps > 16) reps = 16;
-    for (int r = -1; r < reps; ++r) {
-        if (enqueue(p, dir, L, bt, width, stream, ev) != HP_OK) return -1.f;
-        if (hip_failed(hipEventSynchronize(ev.stop))) return -1.f;
-        float ms = 0.f;
-        if (hip_failed(hipEventElapsedTime(&ms, ev.start, ev.stop))) return -1.f;
-        if (r >= 0) t[r] = ms;
+// Four events for timing a burst: the first dispatch carries (e[0], e[1]), the
+// last (e[2], e[3]).
+struct BurstEvents {
+    hipEvent_t e[4] = {nullptr, nullptr, nullptr, nullptr};
+    bool create() {
+        for (hipEvent_t &x : e)
+            if (hip_failed(hipEventCreate(&x))) return false;
+        return true;
     }
-    std::sort(t, t + reps);
-    return median ? t[reps / 2] : t[0];
+    ~BurstEvents() {
+        for (hipEvent_t x : e)
+            if (x) (void)hipEventDestroy(x);
+    }
+};
+
+// Steady-state cost of one launch of a candidate: after a warm-up launch, `burst`
+// launches are enqueued back to back with no host wait in between, and the time
+// from the begin of the first dispatch to the end of the last is divided by
+// `burst`.  Timing isolated launches would flatter shapes that leave work behind
+// (dirty lines still draining to HBM when the kernel ends): that work is paid by
+// whatever runs next, so it has to land inside the measured span.  Returns the
+// median over `bursts` bursts in milliseconds, or a negative value on a HIP error.
+float time_candidate(const hp_plan *p, Direction dir, const hp::Launch &L, const BufTable &bt, int lane,
+                     hipStream_t stream, const BurstEvents &ev, int bursts, int burst) {
+    float t[8];
+    if (bursts > 8) bursts = 8;
+    if (burst < 2) burst = 2;
+    if (enqueue(p, dir, L, bt, lane, stream, EventPair{}) != HP_OK) return -1.f;      // warm-up
+    for (int b = 0; b < bursts; ++b) {
+        for (int i = 0; i < burst; ++i) {
+            EventPair pair;
+            if (i == 0) pair = EventPair{ev.e[0], ev.e[1]};
+            else if (i == burst - 1) pair = EventPair{ev.e[2], ev.e[3]};
+            if (enqueue(p, dir, L, bt, lane, stream, pair) != HP_OK) return -1.f;
+        }
+        if (hip_failed(hipEventSynchronize(ev.e[3]))) return -1.f;
+        float ms = 0.f;
+        if (hip_failed(hipEventElapsedTime(&ms, ev.e[0], ev.e[3]))) return -1.f;
+        t[b] = ms / (float)burst;
+    }
+    std::sort(t, t + bursts);
+    return t[bursts / 2];
 }
 
 // Searches the launch shapes that matter for a streaming kernel on this chip:
 // tile size x workgroup size (1, 2 or 4 sixteen-byte chunks per lane) x the
 // resident-wave cap, keeping the plan's cache policy.  A coarse pass ranks all
-// shapes on two launches each; the best few and the current shape are then
-// re-timed by the median of seven launches, because the top of the ranking is
-// flat and single timings are noisy.
-int tune_direction(hp_plan *p, Direction dir, const BufTable &bt, int width, hipStream_t stream) {
-    hipEvent_t e0 = nullptr, e1 = nullptr;
-    if (hip_failed(hipEventCreate(&e0))) return HP_EHIP;
-    if (hip_failed(hipEventCreate(&e1))) { (void)hipEventDestroy(e0); return HP_EHIP; }
-    const EventPair ev{e0, e1};
-    hp::Launch &cur = dir == kForward ? p->fwd : p->bwd;
+// shapes on one burst of three launches each; the best few and the current
+// shape are then re-timed by the median of three bursts of four, because the top
+// of the ranking is flat and single timings are noisy.
+int tune_direction(hp_plan *p, Direction dir, const BufTable &bt, int lane, hipStream_t stream) {
+    BurstEvents ev;
+    if (!ev.create()) return HP_EHIP;
+    hp::Launch &cur = dir == kForward ? p->fwd : dir == kBackward ? p->bwd : p->acc;
     struct Cand { float ms; hp::Launch L; };
     std::vector<Cand> cands;
     int rc = HP_OK;
@@ -805,7 +834,7 @@ int tune_direction(hp_plan *p, Direction dir, const BufTable &bt, int width, hip
             for (int cap : caps) {
                 if (cap && cap < 2 * (b / 64)) continue;                // cap below two workgroups
                 const hp::Launch L{v, b, cap, cur.nontemporal};
-                const float ms = time_candidate(p, dir, L, bt, width, stream, ev, 2, false);
+                const float ms = time_candidate(p, dir, L, bt, lane, stream, ev, 1, 3);
                 if (ms < 0) { rc = HP_EHIP; break; }
                 cands.push_back(Cand{ms, L});
             }
@@ -819,18 +848,28 @@ int tune_direction(hp_plan *p, Direction dir, const BufTable &bt, int width, hip
         hp::Launch best = cur;
         float best_ms = 1e30f;
         for (const Cand &c : cands) {
-            const float ms = time_candidate(p, dir, c.L, bt, width, stream, ev, 7, true);
+            const float ms = time_candidate(p, dir, c.L, bt, lane, stream, ev, 3, 4);
             if (ms < 0) { rc = HP_EHIP; break; }
             if (ms < best_ms) { best_ms = ms; best = c.L; }
         }
         if (rc == HP_OK) cur = best;
     }
-    (void)hipEventDestroy(e0);
-    (void)hipEventDestroy(e1);
+    if (hip_failed(hipStreamSynchronize(stream))) rc = HP_EHIP;
     return rc;
 }
 
-float time_probe(const ProbeArgs &a, const hp::Launch &L, hipStream_t stream, EventPair ev, int reps) {
+void launch_probe(const ProbeArgs &args, const LaunchCfg &c, int nontemporal) {
+    switch (nontemporal & 3) {
+        case 0: HP_LAUNCH((hp_probe_kernel<false, false>), c, args); break;
+        case 1: HP_LAUNCH((hp_probe_kernel<true, false>), c, args); break;
+        case 2: HP_LAUNCH((hp_probe_kernel<false, true>), c, args); break;
+        default: HP_LAUNCH((hp_probe_kernel<true, true>), c, args); break;
+    }
+}
+
+// Same steady-state burst timing as time_candidate, for the probe kernel.
+float time_probe(const ProbeArgs &a, const hp::Launch &L, hipStream_t stream, const BurstEvents &ev,
+                 int bursts, int burst) {
     ProbeArgs args = a;
     args.chunks_per_wg = hp::tile_bytes_of(L.tile_variant) / 16u;
     LaunchCfg c;
@@ -838,21 +877,23 @@ float time_probe(const ProbeArgs &a, const hp::Launch &L, hipStream_t stream, Ev
     c.block = dim3((unsigned)L.block);
     c.lds_bytes = lds_for_cap(L.block, L.waves_per_cu);
     c.stream = stream;
-    c.ev = ev;
-    float best = 1e30f;
-    for (int r = 0; r < reps + 1; ++r) {
-        switch (L.nontemporal & 3) {
-            case 0: HP_LAUNCH((hp_probe_kernel<false, false>), c, args); break;
-            case 1: HP_LAUNCH((hp_probe_kernel<true, false>), c, args); break;
-            case 2: HP_LAUNCH((hp_probe_kernel<false, true>), c, args); break;
-            default: HP_LAUNCH((hp_probe_kernel<true, true>), c, args); break;
+    float t[8];
+    if (bursts > 8) bursts = 8;
+    launch_probe(args, c, L.nontemporal);                                 // warm-up
+    for (int b = 0; b < bursts; ++b) {
+        for (int i = 0; i < burst; ++i) {
+            c.ev = EventPair{};
+            if (i == 0) c.ev = EventPair{ev.e[0], ev.e[1]};
+            else if (i == burst - 1) c.ev = EventPair{ev.e[2], ev.e[3]};
+            launch_probe(args, c, L.nontemporal);
         }
-        if (hip_failed(hipGetLastError()) || hip_failed(hipEventSynchronize(ev.stop))) return -1.f;
+        if (hip_failed(hipGetLastError()) || hip_failed(hipEventSynchronize(ev.e[3]))) return -1.f;
         float ms = 0.f;
-        if (hip_failed(hipEventElapsedTime(&ms, ev.start, ev.stop))) return -1.f;
-        if (r > 0) best = std::min(best, ms);
+        if (hip_failed(hipEventElapsedTime(&ms, ev.e[0], ev.e[3]))) return -1.f;
+        t[b] = ms / (float)burst;
     }
-    return best;
+    std::sort(t, t + bursts);
+    return t[bursts / 2];
 }
 
 }  // namespace
@@ -924,8 +965,8 @@ int hp_plan_segments(const hp_plan_t *p, hp_segment_t *out, int32_t cap) {
 }
 
 int hp_plan_get_launch(const hp_plan_t *p, int32_t direction, hp_launch_t *out) {
-    if (!p || !out || (direction != 0 && direction != 1)) return HP_EINVAL;
-    const hp::Launch &L = direction == 0 ? p->fwd : p->bwd;
+    if (!p || !out || direction < 0 || direction > 2) return HP_EINVAL;
+    const hp::Launch &L = direction == 0 ? p->fwd : direction == 1 ? p->bwd : p->acc;
     out->tile_bytes = (int32_t)hp::tile_bytes_of(L.tile_variant);
     out->block_threads = L.block;
     out->waves_per_cu = L.waves_per_cu;
@@ -934,10 +975,10 @@ int hp_plan_get_launch(const hp_plan_t *p, int32_t direction, hp_launch_t *out) 
 }
 
 int hp_plan_set_launch(hp_plan_t *p, int32_t direction, const hp_launch_t *in) {
-    if (!p || !in || (direction != 0 && direction != 1)) return HP_EINVAL;
+    if (!p || !in || direction < 0 || direction > 2) return HP_EINVAL;
     hp::Launch L{hp::tile_variant_of(in->tile_bytes), in->block_threads, in->waves_per_cu, in->nontemporal};
     if (!launch_ok(L)) return HP_EINVAL;
-    (direction == 0 ? p->fwd : p->bwd) = L;
+    (direction == 0 ? p->fwd : direction == 1 ? p->bwd : p->acc) = L;
     return HP_OK;
 }
 
@@ -964,7 +1005,7 @@ int hp_backward_accumulate(const hp_plan_t *p, const void *const *dst_grad_bufs,
     int lane = 0;
     int rc = prepare(p, kBackwardAcc, (const void *const *)src_accum_bufs, dst_grad_bufs, &bt, &lane);
     if (rc != HP_OK || p->segments.empty()) return rc;
-    return enqueue(p, kBackwardAcc, p->bwd, bt, lane, (hipStream_t)stream, next_event_pair(2));
+    return enqueue(p, kBackwardAcc, p->acc, bt, lane, (hipStream_t)stream, next_event_pair(2));
 }
 
 int hp_plan_tune(hp_plan_t *p, const void *const *src_bufs, void *const *dst_bufs,
@@ -1004,7 +1045,7 @@ int hp_probe_stream(int32_t n_read, int32_t n_write, int64_t bytes_per_array, co
     a.n_write = (uint32_t)n_write;
     a.n_chunks = (uint64_t)bytes_per_array / 16u;
     void *mem[16] = {nullptr};
-    hipEvent_t e0 = nullptr, e1 = nullptr;
+    BurstEvents ev;
     hipStream_t stream = nullptr;
     int rc = HP_OK;
     for (int i = 0; i < n_read + n_write && rc == HP_OK; ++i) {
@@ -1015,15 +1056,12 @@ int hp_probe_stream(int32_t n_read, int32_t n_write, int64_t bytes_per_array, co
     }
     for (int i = 0; i < n_read; ++i) a.rd[i] = (const u32x4 *)mem[i];
     for (int i = 0; i < n_write; ++i) a.wr[i] = (u32x4 *)mem[n_read + i];
-    if (rc == HP_OK && (hip_failed(hipEventCreate(&e0)) || hip_failed(hipEventCreate(&e1)) ||
-                        hip_failed(hipStreamCreate(&stream))))
-        rc = HP_EHIP;
+    if (rc == HP_OK && (!ev.create() || hip_failed(hipStreamCreate(&stream)))) rc = HP_EHIP;
     float best_ms = 1e30f;
     hp::Launch best = fixed;
     if (rc == HP_OK) {
-        const EventPair ev{e0, e1};
         if (shape) {
-            best_ms = time_probe(a, fixed, stream, ev, 5);
+            best_ms = time_probe(a, fixed, stream, ev, 3, 4);
             if (best_ms < 0) rc = HP_EHIP;
         } else {
             const int blocks[] = {64, 128, 256};
@@ -1036,7 +1074,7 @@ int hp_probe_stream(int32_t n_read, int32_t n_write, int64_t bytes_per_array, co
                     for (int cap : caps) {
                         if (cap && cap < 2 * (b / 64)) continue;
                         const hp::Launch L{v, b, cap, nt};
-                        const float ms = time_probe(a, L, stream, ev, 3);
+                        const float ms = time_probe(a, L, stream, ev, 1, 3);
                         if (ms < 0) { rc = HP_EHIP; break; }
                         if (ms < best_ms) { best_ms = ms; best = L; }
                     }
@@ -1044,9 +1082,12 @@ int hp_probe_stream(int32_t n_read, int32_t n_write, int64_t bytes_per_array, co
                 }
         }
     }
+    if (rc == HP_OK && !shape) {                                          // confirm the winner
+        const float again = time_probe(a, best, stream, ev, 3, 4);
+        if (again < 0) rc = HP_EHIP;
+        else best_ms = again;
+    }
     if (stream) { (void)hipStreamSynchronize(stream); (void)hipStreamDestroy(stream); }
-    if (e0) (void)hipEventDestroy(e0);
-    if (e1) (void)hipEventDestroy(e1);
     for (void *m : mem) if (m) (void)hipFree(m);
     if (rc != HP_OK) return rc;
     *gbps_out = (double)(n_read + n_write) * (double)bytes_per_array / ((double)best_ms * 1e-3) / 1e9;
@@ -1057,6 +1098,18 @@ int hp_probe_stream(int32_t n_read, int32_t n_write, int64_t bytes_per_array, co
         best_shape->nontemporal = best.nontemporal;
     }
     return HP_OK;
+}
+
+int hp_plan_tune_accumulate(hp_plan_t *p, const void *const *dst_grad_bufs, void *const *src_accum_bufs,
+                            void *stream) {
+    if (!p || !dst_grad_bufs || !src_accum_bufs) return HP_EINVAL;
+    if (p->segments.empty()) return HP_OK;
+    BufTable bt;
+    int lane = 0;
+    int rc = prepare(p, kBackwardAcc, (const void *const *)src_accum_bufs, dst_grad_bufs, &bt, &lane);
+    if (rc == HP_OK) rc = tune_direction(p, kBackwardAcc, bt, lane, (hipStream_t)stream);
+    if (rc == HP_OK) g_shapes.remember(p, false, false, true);
+    return rc;
 }
 
 int hp_set_option(const char *key, int64_t value) {

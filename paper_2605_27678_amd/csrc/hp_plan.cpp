@@ -262,6 +262,8 @@ int build_host_plan(const hp_layout_t *src, const hp_layout_t *dst,
                     (int32_t)o.waves_per_cu_fwd, (int32_t)o.nontemporal_fwd};
     p->bwd = Launch{tile_variant_of(o.tile_bytes_bwd), (int32_t)o.block_threads_bwd,
                     (int32_t)o.waves_per_cu_bwd, (int32_t)o.nontemporal_bwd};
+    p->acc = p->bwd;
+    p->acc.tile_variant = std::max(p->acc.tile_variant, 2);   // the read-modify-write side prefers >= 4 KiB tiles
     return make_tables(p);
 }
 

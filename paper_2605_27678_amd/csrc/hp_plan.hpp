@@ -64,7 +64,7 @@ struct hp_plan {
     std::vector<hp_segment_t> segments;   // public view (rows)
     std::vector<hp::Seg> dsegs;           // device view (bytes)
     std::vector<uint32_t> first_tile;     // kTileVariants x (n_segments + 1), row-major
-    hp::Launch fwd{}, bwd{};
+    hp::Launch fwd{}, bwd{}, acc{};       // hp_forward, hp_backward, hp_backward_accumulate
     // device side
     hp::Seg *d_segs = nullptr;
     uint32_t *d_first = nullptr;

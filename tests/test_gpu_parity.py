@@ -490,3 +490,24 @@ def test_plans_rebuilt_every_step_reuse_device_blocks():
         for j in range(4):
             assert np.array_equal(_to_host_bits(g_dst[j]), want[j]), (step, j)
     hp.hp_release_cached_memory()
+
+
+def test_batched_plan_at_the_buffer_limit():
+    """56 microbatches x (4 source + 4 destination) buffers = 448 pointers, the
+    most one plan accepts; one more microbatch is refused."""
+    w = wl.non_colocated(n_microbatches=57)
+    big = replace(w, maps=w.maps[:56])
+    plan = _batched_case(big, 64, seed=3)
+    assert plan.info.n_src_bufs + plan.info.n_dst_bufs == 448
+    with pytest.raises(hp.HpError):
+        hp.hp_plan_create_batched(w.src, w.dst, [replace(m, hidden=64) for m in w.maps])
+
+
+def test_sequence_sharded_destination_long_context_spans():
+    """Config-3 spans with TP ranks holding sequence shards: pieces of 4096
+    positions, so spans are cut at zigzag chunk borders and at shard borders."""
+    w = wl.long_context()
+    tm = replace(w.maps[0], hidden=192)
+    info = check_case(w.src, replace(w.dst, tp_mode=wl.TP_SEQ_SHARD), tm, seed=12)
+    assert info.dst_copies == 1 and info.dst_rows_per_buf == 4096
+    check_case(w.src, replace(w.dst, tp_mode=wl.TP_SEQ_SHARD, cp_split=wl.CP_CONTIGUOUS), tm, seed=13)
