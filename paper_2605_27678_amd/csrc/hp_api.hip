@@ -3,8 +3,8 @@
 // Both kernels are HBM-bound row movers (no dense contraction anywhere, so no
 // MFMA).  A launch cuts every segment of the plan into tiles of a few KiB and
 // runs one short-lived workgroup per tile; a workgroup finds its segment with a
-// scalar binary search over a cache-resident prefix array, then moves its tile
-// with 16-byte lanes.  Forward reads every boundary byte exactly once and
+// scalar 16-ary search over a cache-resident tree of tile prefixes (one 64-byte
+// scalar load per level), then moves its tile with 16-byte lanes.  Forward reads every boundary byte exactly once and
 // stores each 16-byte chunk to all destination TP copies from registers;
 // backward loads the chunk from all copies, folds them in binary32 in ascending
 // tp order inside one lane (a lane owns the same eight elements of every
@@ -42,9 +42,10 @@ struct BufTable {
 
 // Everything else a kernel needs, also by value.
 struct KParams {
-    const hp::Seg *segs;        // n_seg descriptors
-    const uint32_t *first;      // n_seg + 1 tile prefix sums for this launch's tile size
-    uint32_t n_seg;
+    const hp::Seg *segs;        // segment descriptors
+    const uint32_t *tree;       // search trees (64-byte aligned nodes of 16 keys)
+    uint32_t n_levels;          // levels of this launch's tree
+    uint32_t level_off[hp::kMaxTreeLevels];   // start of each level, in keys; level 0 = leaves
     uint32_t tile_bytes;
     uint32_t row_bytes;
     uint32_t rows_per_tile;     // for row-strided segments: max(1, tile_bytes / row_bytes)
@@ -75,15 +76,37 @@ struct TileView {
     uint32_t src_buf, dst_buf0;
 };
 
-// Scalar code: every value here is uniform over the workgroup.
+// One node of the search tree: 16 ascending keys (padding = UINT32_MAX) fetched
+// with one 64-byte scalar load.  Returns how many keys are <= tile, and the
+// largest of them.
+__device__ __forceinline__ void search_node(const uint32_t *node, uint32_t tile, uint32_t &count, uint32_t &key) {
+    const uint32_t *p = (const uint32_t *)__builtin_assume_aligned(node, 64);
+    uint32_t c = 0, best = 0;
+#pragma unroll
+    for (int j = 0; j < hp::kTreeFanout; ++j) {
+        const uint32_t v = p[j];
+        const bool le = v <= tile;
+        c += le ? 1u : 0u;
+        best = le ? v : best;
+    }
+    count = c;
+    key = best;
+}
+
+// Scalar code: every value here is uniform over the workgroup.  One dependent
+// scalar load per tree level, then the descriptor, then the buffer pointers.
 __device__ __forceinline__ TileView locate_tile(const KParams &k, uint32_t tile) {
-    uint32_t lo = 0, hi = k.n_seg;            // first[lo] <= tile < first[hi]
-    while (hi - lo > 1) {
-        const uint32_t mid = (lo + hi) >> 1;
-        if (k.first[mid] <= tile) lo = mid; else hi = mid;
+    uint32_t lo = 0, first = 0;
+#pragma unroll
+    for (int l = hp::kMaxTreeLevels - 1; l >= 0; --l) {
+        if ((uint32_t)l < k.n_levels) {
+            uint32_t count;
+            search_node(k.tree + k.level_off[l] + (size_t)lo * hp::kTreeFanout, tile, count, first);
+            lo = lo * hp::kTreeFanout + count - 1;
+        }
     }
     const hp::Seg s = k.segs[lo];
-    const uint32_t t = tile - k.first[lo];
+    const uint32_t t = tile - first;
     TileView v;
     v.pitch_rows = s.pitch_rows;
     v.src_buf = s.src_buf;
@@ -134,7 +157,7 @@ __device__ __forceinline__ void forward_group(const BufTable &bufs, const KParam
 
 template <typename V, int NREP, bool NTL, bool NTS>
 __global__ void __launch_bounds__(1024)
-hp_forward_kernel(const BufTable bufs, const KParams k) {
+hp_forward_kernel(const KParams k, const BufTable bufs) {
     const TileView t = locate_tile(k, blockIdx.x);
     const uint32_t nrep = NREP > 0 ? (uint32_t)NREP : k.dst_copies;
     const char *src = (const char *)bufs.p[t.src_buf] + t.src_off;
@@ -322,7 +345,7 @@ __device__ __forceinline__ void backward_group(const BufTable &bufs, const KPara
 
 template <int DT, int E, bool ACC, int NREP, bool NTL, bool NTS>
 __global__ void __launch_bounds__(1024)
-hp_backward_kernel(const BufTable bufs, const KParams k) {
+hp_backward_kernel(const KParams k, const BufTable bufs) {
     const TileView t = locate_tile(k, blockIdx.x);
     const uint32_t nrep = NREP > 0 ? (uint32_t)NREP : k.dst_copies;
     const uint32_t n = t.nbytes / (uint32_t)Elems<DT, E>::kBytes;   // lane chunks in this tile, >= 1
@@ -461,11 +484,11 @@ unsigned lds_for_cap(int block, int waves_per_cu) {
 template <typename V, bool NTL, bool NTS>
 void launch_forward_nrep(int copies, const LaunchCfg &c, const BufTable &bt, const KParams &k) {
     switch (copies) {
-        case 1: HP_LAUNCH((hp_forward_kernel<V, 1, NTL, NTS>), c, bt, k); break;
-        case 2: HP_LAUNCH((hp_forward_kernel<V, 2, NTL, NTS>), c, bt, k); break;
-        case 4: HP_LAUNCH((hp_forward_kernel<V, 4, NTL, NTS>), c, bt, k); break;
-        case 8: HP_LAUNCH((hp_forward_kernel<V, 8, NTL, NTS>), c, bt, k); break;
-        default: HP_LAUNCH((hp_forward_kernel<V, 0, NTL, NTS>), c, bt, k); break;
+        case 1: HP_LAUNCH((hp_forward_kernel<V, 1, NTL, NTS>), c, k, bt); break;
+        case 2: HP_LAUNCH((hp_forward_kernel<V, 2, NTL, NTS>), c, k, bt); break;
+        case 4: HP_LAUNCH((hp_forward_kernel<V, 4, NTL, NTS>), c, k, bt); break;
+        case 8: HP_LAUNCH((hp_forward_kernel<V, 8, NTL, NTS>), c, k, bt); break;
+        default: HP_LAUNCH((hp_forward_kernel<V, 0, NTL, NTS>), c, k, bt); break;
     }
 }
 
@@ -481,11 +504,11 @@ void launch_forward_width(int width, int copies, const LaunchCfg &c, const BufTa
 template <int DT, int E, bool ACC, bool NTL, bool NTS>
 void launch_backward_nrep(int copies, const LaunchCfg &c, const BufTable &bt, const KParams &k) {
     switch (copies) {
-        case 1: HP_LAUNCH((hp_backward_kernel<DT, E, ACC, 1, NTL, NTS>), c, bt, k); break;
-        case 2: HP_LAUNCH((hp_backward_kernel<DT, E, ACC, 2, NTL, NTS>), c, bt, k); break;
-        case 4: HP_LAUNCH((hp_backward_kernel<DT, E, ACC, 4, NTL, NTS>), c, bt, k); break;
-        case 8: HP_LAUNCH((hp_backward_kernel<DT, E, ACC, 8, NTL, NTS>), c, bt, k); break;
-        default: HP_LAUNCH((hp_backward_kernel<DT, E, ACC, 0, NTL, NTS>), c, bt, k); break;
+        case 1: HP_LAUNCH((hp_backward_kernel<DT, E, ACC, 1, NTL, NTS>), c, k, bt); break;
+        case 2: HP_LAUNCH((hp_backward_kernel<DT, E, ACC, 2, NTL, NTS>), c, k, bt); break;
+        case 4: HP_LAUNCH((hp_backward_kernel<DT, E, ACC, 4, NTL, NTS>), c, k, bt); break;
+        case 8: HP_LAUNCH((hp_backward_kernel<DT, E, ACC, 8, NTL, NTS>), c, k, bt); break;
+        default: HP_LAUNCH((hp_backward_kernel<DT, E, ACC, 0, NTL, NTS>), c, k, bt); break;
     }
 }
 
@@ -518,11 +541,11 @@ enum Direction { kForward = 0, kBackward = 1, kBackwardAcc = 2 };
 // lane chunk chosen by prepare(): bytes for forward, elements for backward.
 int enqueue(const hp_plan *p, Direction dir, const hp::Launch &L, const BufTable &bt, int lane,
             hipStream_t stream, EventPair ev) {
-    const size_t n_seg = p->segments.size();
     KParams k;
     k.segs = p->d_segs;
-    k.first = p->d_first + (size_t)L.tile_variant * (n_seg + 1);
-    k.n_seg = (uint32_t)n_seg;
+    k.tree = p->d_tree;
+    k.n_levels = p->tree_info[L.tile_variant].n_levels;
+    for (int l = 0; l < hp::kMaxTreeLevels; ++l) k.level_off[l] = p->tree_info[L.tile_variant].level_off[l];
     k.tile_bytes = hp::tile_bytes_of(L.tile_variant);
     k.row_bytes = (uint32_t)p->row_bytes;
     k.rows_per_tile = std::max<uint32_t>(1u, k.tile_bytes / k.row_bytes);
@@ -725,15 +748,15 @@ int create_common(const hp_layout_t *src, const hp_layout_t *dst, const hp_token
         if (rc == HP_OK) g_shapes.apply(p);
         if (rc == HP_OK && !p->segments.empty()) {
             // descriptors and prefix arrays go up in one copy
-            const size_t seg_bytes = p->dsegs.size() * sizeof(hp::Seg);
-            const size_t first_bytes = p->first_tile.size() * sizeof(uint32_t);
+            const size_t seg_bytes = (p->dsegs.size() * sizeof(hp::Seg) + 63) / 64 * 64;   // keep tree nodes 64-byte aligned
+            const size_t first_bytes = p->tree.size() * sizeof(uint32_t);
             try {
                 std::vector<char> staging(seg_bytes + first_bytes);
-                std::memcpy(staging.data(), p->dsegs.data(), seg_bytes);
-                std::memcpy(staging.data() + seg_bytes, p->first_tile.data(), first_bytes);
+                std::memcpy(staging.data(), p->dsegs.data(), p->dsegs.size() * sizeof(hp::Seg));
+                std::memcpy(staging.data() + seg_bytes, p->tree.data(), first_bytes);
                 p->d_segs = (hp::Seg *)g_pool.get(staging.size(), p->device, &p->d_bytes, &rc);
                 if (rc == HP_OK) {
-                    p->d_first = (uint32_t *)((char *)p->d_segs + seg_bytes);
+                    p->d_tree = (uint32_t *)((char *)p->d_segs + seg_bytes);
                     if (hip_failed(hipMemcpy(p->d_segs, staging.data(), staging.size(), hipMemcpyHostToDevice)))
                         rc = HP_EHIP;
                 }
@@ -844,6 +867,20 @@ int tune_direction(hp_plan *p, Direction dir, const BufTable &bt, int lane, hipS
     if (rc == HP_OK) {
         std::sort(cands.begin(), cands.end(), [](const Cand &x, const Cand &y) { return x.ms < y.ms; });
         if (cands.size() > 5) cands.resize(5);
+        // the optimum in the cap is narrow: add the neighbouring caps of the two best shapes
+        const size_t n_top = std::min<size_t>(2, cands.size());
+        for (size_t i = 0; i < n_top; ++i) {
+            const hp::Launch base = cands[i].L;
+            const int per_wg = base.block / 64;
+            const int centre = base.waves_per_cu == 0 ? 32 : base.waves_per_cu;
+            for (int d = -2; d <= 2; ++d) {
+                if (d == 0) continue;
+                int cap = centre + d * per_wg;
+                if (cap < 2 * per_wg || cap > 32) continue;
+                if (cap == 32) cap = 0;
+                cands.push_back(Cand{0.f, hp::Launch{base.tile_variant, base.block, cap, base.nontemporal}});
+            }
+        }
         cands.push_back(Cand{0.f, cur});
         hp::Launch best = cur;
         float best_ms = 1e30f;

@@ -167,6 +167,28 @@ int make_tables(hp_plan *p) {
         }
         row[n] = (uint32_t)acc;
     }
+    // 16-ary search trees over the keys of each variant
+    p->tree.clear();
+    for (int v = 0; v < kTileVariants && n > 0; ++v) {
+        const uint32_t *keys = p->first_tile.data() + (size_t)v * (n + 1);
+        std::vector<std::vector<uint32_t>> levels;
+        levels.emplace_back(keys, keys + n);
+        while (levels.back().size() > (size_t)kTreeFanout) {
+            const std::vector<uint32_t> &below = levels.back();
+            std::vector<uint32_t> up;
+            for (size_t j = 0; j < below.size(); j += kTreeFanout) up.push_back(below[j]);
+            levels.push_back(std::move(up));
+        }
+        if (levels.size() > (size_t)kMaxTreeLevels) return HP_ELAYOUT;
+        TreeInfo &ti = p->tree_info[v];
+        ti.n_levels = (uint32_t)levels.size();
+        for (size_t l = 0; l < levels.size(); ++l) {
+            std::vector<uint32_t> &lv = levels[l];
+            lv.resize((lv.size() + kTreeFanout - 1) / kTreeFanout * kTreeFanout, 0xffffffffu);
+            ti.level_off[l] = (uint32_t)p->tree.size();
+            p->tree.insert(p->tree.end(), lv.begin(), lv.end());
+        }
+    }
     return HP_OK;
 }
 

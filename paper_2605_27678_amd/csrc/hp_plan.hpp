@@ -24,10 +24,22 @@ static_assert(sizeof(Seg) == 32, "segment descriptor must stay 32 bytes");
 
 // A launch cuts every segment into tiles of 1 KiB << v bytes, one workgroup per
 // tile.  For each variant v the plan keeps first_tile[v][s] = number of tiles of
-// segments 0..s-1, so a workgroup finds its segment by a binary search over a
-// tiny, cache-resident array instead of reading a per-tile table from HBM.
+// segments 0..s-1 and, for the device, a 16-ary search tree over those keys, so
+// a workgroup finds its segment with one 64-byte scalar load per tree level
+// (one level up to 16 segments, two up to 256, ...) out of a tiny,
+// cache-resident table instead of reading a per-tile table from HBM.
 constexpr int kTileVariants = 7;
+constexpr int kTreeFanout = 16;
+constexpr int kMaxTreeLevels = 4;          // 16^4 = 65536 segments
 inline uint32_t tile_bytes_of(int v) { return 1024u << v; }
+
+// Where one variant's search tree sits in the plan's tree array (in uint32
+// elements).  Level 0 holds the keys first_tile[v][0..n), padded with
+// UINT32_MAX to whole 16-key nodes; key j of level l+1 is key 16*j of level l.
+struct TreeInfo {
+    uint32_t n_levels;
+    uint32_t level_off[kMaxTreeLevels];
+};
 
 // How one direction is launched.  Lives in the plan; seeded from the
 // process-wide defaults, overridden by hp_plan_set_launch or hp_plan_tune.
@@ -41,8 +53,8 @@ struct Launch {
 struct Options {
     // defaults = what hp_plan_tune picks most often on the long-context workload
     int64_t tile_bytes_fwd = 2048, tile_bytes_bwd = 1024;
-    int64_t block_threads_fwd = 128, block_threads_bwd = 64;
-    int64_t waves_per_cu_fwd = 16, waves_per_cu_bwd = 16;   // 0 = no cap
+    int64_t block_threads_fwd = 64, block_threads_bwd = 64;
+    int64_t waves_per_cu_fwd = 12, waves_per_cu_bwd = 16;   // 0 = no cap
     int64_t nontemporal_fwd = 2, nontemporal_bwd = 3;       // bit 0 loads, bit 1 stores
 };
 Options &options();
@@ -64,10 +76,12 @@ struct hp_plan {
     std::vector<hp_segment_t> segments;   // public view (rows)
     std::vector<hp::Seg> dsegs;           // device view (bytes)
     std::vector<uint32_t> first_tile;     // kTileVariants x (n_segments + 1), row-major
+    std::vector<uint32_t> tree;           // the search trees of all variants, 64-byte aligned nodes
+    hp::TreeInfo tree_info[hp::kTileVariants] = {};
     hp::Launch fwd{}, bwd{}, acc{};       // hp_forward, hp_backward, hp_backward_accumulate
     // device side
     hp::Seg *d_segs = nullptr;
-    uint32_t *d_first = nullptr;
+    uint32_t *d_tree = nullptr;
     size_t d_bytes = 0;                   // size of the device block behind d_segs
     int device = -1;
 
