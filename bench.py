@@ -51,7 +51,10 @@ def main() -> int:
     ap.add_argument("--steps", type=int, default=15)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="long_context",
-                    choices=["tiny", "colocated4", "long_context", "non_colocated", "large_scale"])
+                    choices=["tiny", "colocated4", "colocated4_dense", "long_context", "non_colocated", "large_scale"])
+    ap.add_argument("--graph", action="store_true",
+                    help="record one step into a HIP graph and time its replays (wall clock); kernel "
+                         "durations still come from eager launches carrying events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-tune", action="store_true",
                     help="keep the default launch shapes instead of calling hp_plan_tune before the timed region")
@@ -152,17 +155,41 @@ def main() -> int:
             else:
                 s["plan"].backward_raw(s["pgd"], s["pgs"], stream)
 
+    timed_step = step
+    if args.graph:
+        step()                                   # first launches outside the capture
+        stream.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=stream):
+            step()
+        timed_step = graph.replay
     for _ in range(args.warmup):
-        step()
+        timed_step()
     stream.synchronize()
     torch.cuda.synchronize()
+    rehearsal = 0
+    if n_launch > 1 and not args.graph:
+        # A step of many launches queues hundreds of dispatches before the closing
+        # synchronisation.  The first device-wide synchronisation after the first
+        # queue that deep has been seen to take 35-40 ms once per process (host
+        # side: the GPU trace shows the kernels back to back and long finished),
+        # so one untimed pass of the same length goes first.
+        rehearsal = args.steps
+        for _ in range(rehearsal):
+            timed_step()
+        stream.synchronize()
+        torch.cuda.synchronize()
     # Timed region: EXACTLY `steps` steps between two synchronisations -> `value`.
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        timed_step()
+    enqueue_s = time.perf_counter() - t0       # host time to submit the steps (inside the timed region)
     stream.synchronize()
+    stream_sync_s = time.perf_counter() - t0
     torch.cuda.synchronize()
     total_s = time.perf_counter() - t0
+    log(f"[bench] timed region: submitted after {enqueue_s * 1e3:.3f} ms, stream synchronised after "
+        f"{stream_sync_s * 1e3:.3f} ms, device synchronised after {total_s * 1e3:.3f} ms")
     # The same `steps` steps again, now with a HIP event pair attached to every
     # launch (stamped by the dispatch itself on the stream it runs on) -> kernel
     # durations for the roofline.  Kept out of the region above because the
@@ -187,7 +214,8 @@ def main() -> int:
     f_med, b_med = statistics.median(fwd_ms), statistics.median(bwd_ms)
     log(f"[bench] kernel time per step: fwd median {f_med:.4f} ms ({fwd_bytes / f_med / 1e6:.0f} GB/s), "
         f"bwd median {b_med:.4f} ms ({bwd_bytes / b_med / 1e6:.0f} GB/s); wall {ms_per_step:.4f} ms/step "
-        f"({value:.0f} GB/s); wall with per-launch events {total_events_s * 1e3 / args.steps:.4f} ms/step")
+        f"({value:.0f} GB/s), of which the host spent {enqueue_s * 1e3 / args.steps:.4f} submitting; "
+        f"wall with per-launch events {total_events_s * 1e3 / args.steps:.4f} ms/step")
 
     # ---- rebuilding the plan at step rate (token maps change every step): warm create + destroy ----
     t0 = time.perf_counter()
@@ -289,6 +317,7 @@ def main() -> int:
                    "tp_mode": "seq_shard" if args.seq_shard else "replicate",
                    "backward": "accumulate_f32" if args.accumulate else "overwrite",
                    "accumulate_dtype": "f32", "launches_per_direction": n_launch, "launch_shapes": shapes, "tuned": not args.no_tune,
+                   "submission": "hip_graph_replay" if args.graph else "eager",
                    "image_rows": int(sum(m.n_rows for m in maps)), "boundary_bytes": boundary,
                    },
         "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
@@ -297,6 +326,9 @@ def main() -> int:
         "backward": {"bytes": bwd_bytes, "median_ms": b_med, "min_ms": min(bwd_ms), "max_ms": max(bwd_ms),
                      "GBps": bwd_bytes / b_med / 1e6, "pct_of_hbm_peak": bwd_bytes / b_med / 1e6 / HBM_PEAK_GBPS * 100},
         "ms_per_step_with_kernel_events": total_events_s * 1e3 / args.steps,
+        "host_submit_ms_per_step": enqueue_s * 1e3 / args.steps,
+        "ms_per_step_to_stream_sync": stream_sync_s * 1e3 / args.steps,
+        "untimed_rehearsal_steps": rehearsal,
         "plan_build_ms": plan_ms, "plan_rebuild_ms": plan_rebuild_ms, "plan_tune_ms": tune_ms,
         "device_copy_GBps": copy_gbps,
         "pattern_ceiling": {"forward_GBps": ceil_f, "backward_GBps": ceil_b, "array_bytes": arr,

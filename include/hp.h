@@ -192,8 +192,13 @@ int hp_plan_create_batched(const hp_layout_t *src, const hp_layout_t *dst,
 /* Frees the host tables and hands the device block (a few KB) back to a small
  * per-process cache from which later hp_plan_create calls on the same device
  * are served, so that plans can be rebuilt at training-step rate without a
- * hipMalloc / hipFree pair each time.  NULL is allowed.  The caller must have
- * synchronised every stream that still uses the plan. */
+ * hipMalloc / hipFree pair each time.  NULL is allowed.  The call may follow the
+ * last hp_forward / hp_backward that uses the plan at once, without any
+ * synchronisation: the block is not overwritten before the streams those calls
+ * were enqueued on have passed them (an event per stream is recorded here and
+ * waited for when the block is next handed out).  Call it with the plan's
+ * device current.  A plan whose calls were recorded into a HIP graph has to
+ * outlive the replays of that graph. */
 void hp_plan_destroy(hp_plan_t *plan);
 
 /* hipFree()s every cached device block (at most 64 blocks of a few KB). */
@@ -281,8 +286,12 @@ int hp_plan_set_launch(hp_plan_t *plan, int32_t direction, const hp_launch_t *in
  * as after one such call.  Candidates are timed as bursts of back-to-back
  * launches, so that work a shape leaves behind at the end of a kernel (dirty
  * lines still draining to HBM) is charged to it and not to the next kernel.
- * SYNCHRONOUS: waits on `stream` repeatedly, takes
- * tens of milliseconds, creates and destroys four HIP events, and must not run
+ * When the buffers of both directions are given, every candidate launch of one
+ * direction is followed by a launch of the other direction with its current
+ * shape, and the pair is what is timed: a shape is judged in the sequence
+ * forward, backward, forward, ... rather than against copies of itself.
+ * SYNCHRONOUS: waits on `stream` repeatedly, takes tens to hundreds of
+ * milliseconds, creates and destroys four HIP events, and must not run
  * concurrently with other calls that use the same plan.
  * The winning shapes are also remembered per problem class (dtype, row size,
  * TP_dst copies, TP_src copies, device): plans of the same class created later

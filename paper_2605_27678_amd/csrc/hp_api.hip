@@ -576,6 +576,7 @@ int enqueue(const hp_plan *p, Direction dir, const hp::Launch &L, const BufTable
         }
     }
     if (hip_failed(hipGetLastError())) return HP_EHIP;
+    p->note_stream((void *)stream);
     return HP_OK;
 }
 
@@ -637,28 +638,42 @@ bool launch_ok(const hp::Launch &L) {
 // step, so plans are created and destroyed at step rate, and a hipMalloc +
 // hipFree pair costs far more than building the tables.  Blocks come in 4 KiB
 // size classes; a destroyed plan's block waits here for the next plan on the
-// same device.
+// same device.  A block may still be read by kernels that were enqueued before
+// its plan was destroyed: it carries one event per stream the plan was used on,
+// recorded at destroy time, and is not overwritten before they have completed.
 struct TablePool {
-    struct Block { void *p; size_t bytes; int device; };
+    struct Block { void *p; size_t bytes; int device; std::vector<hipEvent_t> pending; };
     std::mutex mu;
     std::vector<Block> free_blocks;
     static constexpr size_t kMaxCached = 64;
 
+    static void wait_and_drop(std::vector<hipEvent_t> &events) {
+        for (hipEvent_t e : events) {
+            (void)hipEventSynchronize(e);
+            (void)hipEventDestroy(e);
+        }
+        events.clear();
+    }
+
     void *get(size_t need, int device, size_t *got, int *rc) {
         need = (need + 4095) / 4096 * 4096;
+        Block b{nullptr, 0, -1, {}};
         {
             std::lock_guard<std::mutex> lk(mu);
-            size_t best = free_blocks.size();
+            size_t best = free_blocks.size();               // smallest that fits; the oldest among equals
             for (size_t i = 0; i < free_blocks.size(); ++i)
                 if (free_blocks[i].device == device && free_blocks[i].bytes >= need &&
                     (best == free_blocks.size() || free_blocks[i].bytes < free_blocks[best].bytes))
                     best = i;
             if (best != free_blocks.size()) {
-                Block b = free_blocks[best];
+                b = std::move(free_blocks[best]);
                 free_blocks.erase(free_blocks.begin() + best);
-                *got = b.bytes;
-                return b.p;
             }
+        }
+        if (b.p) {
+            wait_and_drop(b.pending);                       // normally long complete
+            *got = b.bytes;
+            return b.p;
         }
         void *p = nullptr;
         hipError_t e = hipMalloc(&p, need);
@@ -667,15 +682,37 @@ struct TablePool {
         *got = need;
         return p;
     }
-    void put(void *p, size_t bytes, int device) {
+
+    // `streams`: where work reading the block was enqueued.  If the order after
+    // that work cannot be recorded (another device is current, a stream is being
+    // captured into a graph, an event call fails) the block is freed instead;
+    // hipFree waits for the device.
+    void put(void *p, size_t bytes, int device, const std::vector<void *> &streams) {
         if (!p) return;
-        {
+        Block b{p, bytes, device, {}};
+        bool ok = true;
+        int cur = -1;
+        if (!streams.empty() && (hipGetDevice(&cur) != hipSuccess || cur != device)) ok = false;
+        for (size_t i = 0; ok && i < streams.size(); ++i) {
+            hipStream_t st = (hipStream_t)streams[i];
+            hipStreamCaptureStatus cs = hipStreamCaptureStatusNone;
+            if (hipStreamIsCapturing(st, &cs) != hipSuccess || cs != hipStreamCaptureStatusNone) { ok = false; break; }
+            hipEvent_t e = nullptr;
+            if (hipEventCreateWithFlags(&e, hipEventDisableTiming) != hipSuccess) { ok = false; break; }
+            b.pending.push_back(e);
+            if (hipEventRecord(e, st) != hipSuccess) ok = false;
+        }
+        if (ok) {
             std::lock_guard<std::mutex> lk(mu);
             if (free_blocks.size() < kMaxCached) {
-                free_blocks.push_back(Block{p, bytes, device});
+                free_blocks.push_back(std::move(b));
                 return;
             }
         }
+        (void)hipGetLastError();
+        if (ok) wait_and_drop(b.pending);
+        else
+            for (hipEvent_t e : b.pending) (void)hipEventDestroy(e);
         (void)hipFree(p);
     }
     void release_all() {
@@ -684,7 +721,10 @@ struct TablePool {
             std::lock_guard<std::mutex> lk(mu);
             blocks.swap(free_blocks);
         }
-        for (const Block &b : blocks) (void)hipFree(b.p);
+        for (Block &b : blocks) {
+            wait_and_drop(b.pending);
+            (void)hipFree(b.p);
+        }
     }
 } g_pool;
 
@@ -766,7 +806,7 @@ int create_common(const hp_layout_t *src, const hp_layout_t *dst, const hp_token
         }
     }
     if (rc != HP_OK) {
-        g_pool.put(p->d_segs, p->d_bytes, p->device);
+        g_pool.put(p->d_segs, p->d_bytes, p->device, {});
         delete p;
         return rc;
     }
@@ -806,25 +846,43 @@ struct BurstEvents {
     }
 };
 
-// Steady-state cost of one launch of a candidate: after a warm-up launch, `burst`
-// launches are enqueued back to back with no host wait in between, and the time
-// from the begin of the first dispatch to the end of the last is divided by
-// `burst`.  Timing isolated launches would flatter shapes that leave work behind
-// (dirty lines still draining to HBM when the kernel ends): that work is paid by
-// whatever runs next, so it has to land inside the measured span.  Returns the
-// median over `bursts` bursts in milliseconds, or a negative value on a HIP error.
+// What runs right after every candidate launch while it is being timed: the
+// plan's other direction with its current launch shape, when the caller gave
+// the buffers of both.  A streaming kernel's speed depends on what the memory
+// system is still doing for its predecessor, so a shape is judged in the
+// sequence the caller will run (forward, backward, forward, ...), not alone.
+struct Companion {
+    Direction dir;
+    hp::Launch L;
+    const BufTable *bt;
+    int lane;
+};
+
+// Steady-state cost of one launch of a candidate (plus its companion, if any):
+// after a warm-up launch, `burst` launches are enqueued back to back with no
+// host wait in between, and the time from the begin of the first dispatch to the
+// end of the last is divided by `burst`.  Timing isolated launches would flatter
+// shapes that leave work behind (dirty lines still draining to HBM when the
+// kernel ends): that work is paid by whatever runs next, so it has to land
+// inside the measured span.  Returns the median over `bursts` bursts in
+// milliseconds, or a negative value on a HIP error.
 float time_candidate(const hp_plan *p, Direction dir, const hp::Launch &L, const BufTable &bt, int lane,
-                     hipStream_t stream, const BurstEvents &ev, int bursts, int burst) {
+                     hipStream_t stream, const BurstEvents &ev, int bursts, int burst, const Companion *co) {
     float t[8];
     if (bursts > 8) bursts = 8;
     if (burst < 2) burst = 2;
     if (enqueue(p, dir, L, bt, lane, stream, EventPair{}) != HP_OK) return -1.f;      // warm-up
+    if (co && enqueue(p, co->dir, co->L, *co->bt, co->lane, stream, EventPair{}) != HP_OK) return -1.f;
     for (int b = 0; b < bursts; ++b) {
         for (int i = 0; i < burst; ++i) {
+            const bool last = i == burst - 1;
             EventPair pair;
             if (i == 0) pair = EventPair{ev.e[0], ev.e[1]};
-            else if (i == burst - 1) pair = EventPair{ev.e[2], ev.e[3]};
+            else if (last && !co) pair = EventPair{ev.e[2], ev.e[3]};
             if (enqueue(p, dir, L, bt, lane, stream, pair) != HP_OK) return -1.f;
+            if (co && enqueue(p, co->dir, co->L, *co->bt, co->lane, stream,
+                              last ? EventPair{ev.e[2], ev.e[3]} : EventPair{}) != HP_OK)
+                return -1.f;
         }
         if (hip_failed(hipEventSynchronize(ev.e[3]))) return -1.f;
         float ms = 0.f;
@@ -838,10 +896,12 @@ float time_candidate(const hp_plan *p, Direction dir, const hp::Launch &L, const
 // Searches the launch shapes that matter for a streaming kernel on this chip:
 // tile size x workgroup size (1, 2 or 4 sixteen-byte chunks per lane) x the
 // resident-wave cap, keeping the plan's cache policy.  A coarse pass ranks all
-// shapes on one burst of three launches each; the best few and the current
-// shape are then re-timed by the median of three bursts of four, because the top
-// of the ranking is flat and single timings are noisy.
-int tune_direction(hp_plan *p, Direction dir, const BufTable &bt, int lane, hipStream_t stream) {
+// shapes on one burst of three launches each; the best few, the neighbouring
+// caps of the best two and the current shape are then re-timed by the median of
+// three bursts of four, because the top of the ranking is flat and single
+// timings are noisy.
+int tune_direction(hp_plan *p, Direction dir, const BufTable &bt, int lane, hipStream_t stream,
+                   const Companion *co) {
     BurstEvents ev;
     if (!ev.create()) return HP_EHIP;
     hp::Launch &cur = dir == kForward ? p->fwd : dir == kBackward ? p->bwd : p->acc;
@@ -857,7 +917,7 @@ int tune_direction(hp_plan *p, Direction dir, const BufTable &bt, int lane, hipS
             for (int cap : caps) {
                 if (cap && cap < 2 * (b / 64)) continue;                // cap below two workgroups
                 const hp::Launch L{v, b, cap, cur.nontemporal};
-                const float ms = time_candidate(p, dir, L, bt, lane, stream, ev, 1, 3);
+                const float ms = time_candidate(p, dir, L, bt, lane, stream, ev, 1, 3, co);
                 if (ms < 0) { rc = HP_EHIP; break; }
                 cands.push_back(Cand{ms, L});
             }
@@ -885,7 +945,7 @@ int tune_direction(hp_plan *p, Direction dir, const BufTable &bt, int lane, hipS
         hp::Launch best = cur;
         float best_ms = 1e30f;
         for (const Cand &c : cands) {
-            const float ms = time_candidate(p, dir, c.L, bt, lane, stream, ev, 3, 4);
+            const float ms = time_candidate(p, dir, c.L, bt, lane, stream, ev, 3, 4, co);
             if (ms < 0) { rc = HP_EHIP; break; }
             if (ms < best_ms) { best_ms = ms; best = c.L; }
         }
@@ -954,7 +1014,7 @@ int hp_plan_create_batched(const hp_layout_t *src, const hp_layout_t *dst, const
 
 void hp_plan_destroy(hp_plan_t *plan) {
     if (!plan) return;
-    g_pool.put(plan->d_segs, plan->d_bytes, plan->device);
+    g_pool.put(plan->d_segs, plan->d_bytes, plan->device, plan->used_streams);
     delete plan;
 }
 
@@ -1051,16 +1111,20 @@ int hp_plan_tune(hp_plan_t *p, const void *const *src_bufs, void *const *dst_buf
     if ((src_bufs == nullptr) != (dst_bufs == nullptr)) return HP_EINVAL;
     if ((dst_grad_bufs == nullptr) != (src_grad_bufs == nullptr)) return HP_EINVAL;
     if (p->segments.empty()) return HP_OK;
-    BufTable bt;
-    int width = 0, rc = HP_OK;
-    if (src_bufs) {
-        rc = prepare(p, kForward, src_bufs, (const void *const *)dst_bufs, &bt, &width);
-        if (rc == HP_OK) rc = tune_direction(p, kForward, bt, width, (hipStream_t)stream);
+    BufTable bt_f, bt_b;
+    int lane_f = 0, lane_b = 0, rc = HP_OK;
+    if (src_bufs) rc = prepare(p, kForward, src_bufs, (const void *const *)dst_bufs, &bt_f, &lane_f);
+    if (rc == HP_OK && dst_grad_bufs)
+        rc = prepare(p, kBackward, (const void *const *)src_grad_bufs, dst_grad_bufs, &bt_b, &lane_b);
+    const bool both = src_bufs && dst_grad_bufs;
+    if (rc == HP_OK && src_bufs) {
+        const Companion co{kBackward, p->bwd, &bt_b, lane_b};
+        rc = tune_direction(p, kForward, bt_f, lane_f, (hipStream_t)stream, both ? &co : nullptr);
         if (rc == HP_OK) g_shapes.remember(p, true, false);
     }
     if (rc == HP_OK && dst_grad_bufs) {
-        rc = prepare(p, kBackward, (const void *const *)src_grad_bufs, dst_grad_bufs, &bt, &width);
-        if (rc == HP_OK) rc = tune_direction(p, kBackward, bt, width, (hipStream_t)stream);
+        const Companion co{kForward, p->fwd, &bt_f, lane_f};
+        rc = tune_direction(p, kBackward, bt_b, lane_b, (hipStream_t)stream, both ? &co : nullptr);
         if (rc == HP_OK) g_shapes.remember(p, false, true);
     }
     return rc;
@@ -1144,7 +1208,7 @@ int hp_plan_tune_accumulate(hp_plan_t *p, const void *const *dst_grad_bufs, void
     BufTable bt;
     int lane = 0;
     int rc = prepare(p, kBackwardAcc, (const void *const *)src_accum_bufs, dst_grad_bufs, &bt, &lane);
-    if (rc == HP_OK) rc = tune_direction(p, kBackwardAcc, bt, lane, (hipStream_t)stream);
+    if (rc == HP_OK) rc = tune_direction(p, kBackwardAcc, bt, lane, (hipStream_t)stream, nullptr);
     if (rc == HP_OK) g_shapes.remember(p, false, false, true);
     return rc;
 }

@@ -1,6 +1,7 @@
 // Internal: host-side plan of the boundary layout transform.
 #pragma once
 #include <cstdint>
+#include <mutex>
 #include <vector>
 
 #include "hp.h"
@@ -84,6 +85,17 @@ struct hp_plan {
     uint32_t *d_tree = nullptr;
     size_t d_bytes = 0;                   // size of the device block behind d_segs
     int device = -1;
+    // Streams on which work that reads the device block has been enqueued (as
+    // opaque handles).  hp_plan_destroy orders the reuse of the block after them.
+    mutable std::mutex use_mu;
+    mutable std::vector<void *> used_streams;
+
+    void note_stream(void *stream) const {
+        std::lock_guard<std::mutex> lk(use_mu);
+        for (void *s : used_streams)
+            if (s == stream) return;
+        used_streams.push_back(stream);
+    }
 
     uint32_t n_tiles(int variant) const {
         const size_t n = segments.size();

@@ -145,6 +145,35 @@ def colocated4(seed: int = BASE_SEED + 2) -> Workload:
     return Workload("colocated4", Grid(tp=1, dp=4), Grid(tp=4, cp=1, dp=1), [tm], seed)
 
 
+def shuffle_spans(rng: np.random.Generator, tm: TokenMap) -> TokenMap:
+    """The same set of spans with, inside every sample, the spans handed to the
+    images in a seeded random order: image k of a sample no longer sits before
+    image k+1 in the sequence.  Source rows stay in image order, so the
+    transform has to follow the token map, not the position order."""
+    samp = np.asarray(tm.img_sample)
+    start = np.asarray(tm.img_start).copy()
+    length = np.asarray(tm.img_len).copy()
+    for b in np.unique(samp):
+        idx = np.flatnonzero(samp == b)
+        perm = rng.permutation(len(idx))
+        start[idx] = start[idx[perm]]
+        length[idx] = length[idx[perm]]
+    return replace(tm, img_start=start.astype(np.int32), img_len=length.astype(np.int32))
+
+
+def colocated4_dense(seed: int = BASE_SEED + 2) -> Workload:
+    """Config 2 under its other reading: the stated sequence length of 8192 is
+    the fused length, so the 8 images x 1024 tokens of a sample tile the whole
+    sequence with no text between them; the images of a sample take the eight
+    slots in a seeded random order."""
+    rng = np.random.default_rng(seed)
+    samp = np.repeat(np.arange(4), 8)
+    start = np.concatenate([rng.permutation(8) * 1024 for _ in range(4)])
+    tm = TokenMap(4, 8192, 4096, samp.astype(np.int32), start.astype(np.int32),
+                  np.full(32, 1024, np.int32))
+    return Workload("colocated4_dense", Grid(tp=1, dp=4), Grid(tp=4, cp=1, dp=1), [tm], seed)
+
+
 def long_context(seed: int = BASE_SEED + 3, n_images: Optional[int] = None) -> Workload:
     """Config 3: vision DP8 -> LLM TP4,CP8 with the load-balanced split; one
     sample of 131072 fused tokens, hidden 5120; image lengths U{256..2304} drawn
@@ -198,6 +227,7 @@ def scaled(w: Workload, hidden: int) -> Workload:
 CONFIGS = {
     "tiny": tiny,
     "colocated4": colocated4,
+    "colocated4_dense": colocated4_dense,
     "long_context": long_context,
     "non_colocated": non_colocated,
     "large_scale": large_scale,

@@ -11,7 +11,7 @@ import torch
 import paper_2605_27678_amd as hp
 from oracle import oracle
 from paper_2605_27678_amd import workloads as wl
-from parity import _to_host_bits, check_case
+from parity import _to_host_bits, check_case, make_inputs
 
 pytestmark = pytest.mark.gpu
 
@@ -43,6 +43,21 @@ def test_random_small_layouts(seed):
     check_case(src, dst, tm, seed=seed)
     if (tm.seq // dst.cp) % dst.tp == 0:
         check_case(src, replace(dst, tp_mode=wl.TP_SEQ_SHARD), tm, seed=seed + 100)
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_spans_out_of_position_order(seed):
+    """Images of a sample placed in the sequence in a shuffled order."""
+    rng = np.random.default_rng(400 + seed)
+    src, dst, tm = wl.random_layout_case(rng)
+    check_case(src, dst, wl.shuffle_spans(rng, tm), seed=seed)
+
+
+@pytest.mark.parametrize("k", [1, 2, 7, 8, 9, 32])
+def test_long_context_image_counts(k):
+    """Config-3 grid with 1..32 images: empty source ranks when k < 8."""
+    w = wl.scaled(wl.long_context(n_images=k), 320)
+    check_case(w.src, w.dst, w.maps[0], seed=k)
 
 
 @pytest.mark.parametrize("hidden", [7, 9, 12, 100, 320, 1000, 5120])
@@ -237,6 +252,13 @@ def test_full_colocated4():
     w = wl.colocated4()
     info = check_case(w.src, w.dst, w.maps[0], seed=2, gen_device="cuda")
     assert info.boundary_bytes == 256 << 20
+
+
+def test_full_colocated4_dense_reading():
+    """Config 2 read with a fused length of 8192: images tile the sequences."""
+    w = wl.colocated4_dense()
+    info = check_case(w.src, w.dst, w.maps[0], seed=22, gen_device="cuda")
+    assert info.boundary_bytes == 256 << 20 and info.n_rows == 4 * 8192
 
 
 def test_full_long_context():
@@ -511,3 +533,42 @@ def test_sequence_sharded_destination_long_context_spans():
     info = check_case(w.src, replace(w.dst, tp_mode=wl.TP_SEQ_SHARD), tm, seed=12)
     assert info.dst_copies == 1 and info.dst_rows_per_buf == 4096
     check_case(w.src, replace(w.dst, tp_mode=wl.TP_SEQ_SHARD, cp_split=wl.CP_CONTIGUOUS), tm, seed=13)
+
+
+def test_plan_destroyed_while_its_calls_are_still_queued():
+    """hp_plan_destroy right after the calls were enqueued, followed by a new
+    plan that takes over the recycled device block: the queued calls must still
+    run on their own tables.  Both token maps have the same span lengths and the
+    same segment and tile structure (spans well inside the sequence chunks, the
+    second map shifted by 37 rows), and all buffers have the same sizes."""
+    H, S = 2048, 65536
+    src, dst = wl.Grid(dp=2), wl.Grid(tp=2, cp=2, cp_split=wl.CP_ZIGZAG)
+    starts = np.array([1000, 20000, 36000, 50000])
+    tm_a = wl.TokenMap(1, S, H, [0] * 4, starts, [6000] * 4)
+    tm_b = wl.TokenMap(1, S, H, [0] * 4, starts + 37, [6000] * 4)
+    prob_a, prob_b = oracle.Problem(src, dst, tm_a), oracle.Problem(src, dst, tm_b)
+    assert prob_a.src_rows() == prob_b.src_rows()
+    hp.hp_release_cached_memory()                         # so that plan b can only get plan a's block
+    plan_a = hp.hp_plan_create(src, dst, tm_a)
+    q = hp.hp_plan_create_host(src, dst, tm_b)
+    assert plan_a.info.n_segments == q.info.n_segments and plan_a.info.n_tiles == q.info.n_tiles
+    q.close()
+    srcs, pre, _ = make_inputs(prob_a, 77, "cuda")
+    dst_a = [t.clone() for t in pre]
+    dst_b = [t.clone() for t in pre]
+    st = torch.cuda.Stream()
+    st.wait_stream(torch.cuda.current_stream())
+    ps, pd = plan_a.pointer_arrays(srcs, dst_a)
+    for _ in range(40):                                   # ~2 ms of queued work
+        plan_a.forward_raw(ps, pd, st)
+    plan_a.close()                                        # no synchronisation before this
+    plan_b = hp.hp_plan_create(src, dst, tm_b)            # reuses the block once the queue has drained
+    hp.hp_forward(plan_b, srcs, dst_b, st)
+    torch.cuda.synchronize()
+    h_src = [_to_host_bits(t) for t in srcs]
+    for prob, got in ((prob_a, dst_a), (prob_b, dst_b)):
+        want = [_to_host_bits(t).copy() for t in pre]
+        prob.forward(h_src, want)
+        for j in range(prob.n_dst):
+            assert np.array_equal(_to_host_bits(got[j]), want[j]), j
+    plan_b.close()

@@ -167,6 +167,44 @@ def test_forward_matches_global_slicing(seed):
 
 
 @pytest.mark.parametrize("seed", range(20))
+def test_forward_matches_global_slicing_spans_out_of_position_order(seed):
+    """Images of a sample need not sit in the sequence in image order: the
+    source keeps image order, the fused sequence follows the token map."""
+    rng = np.random.default_rng(7000 + seed)
+    src, dst, tm = wl.random_layout_case(rng)
+    tm = wl.shuffle_spans(rng, tm)
+    X = row_id_payload(tm.n_rows, tm.hidden)
+    prob, srcs, dsts = run_oracle_forward(src, dst, tm, X)
+    want, _ = brute_forward(src, dst, tm, X, 0xFFFF)
+    for j in range(prob.n_dst):
+        assert np.array_equal(dsts[j], want[j]), (seed, j)
+
+
+def test_dense_reading_of_config_2_tiles_the_sequence():
+    """8 images x 1024 tokens filling a sequence of 8192 with no text: every
+    destination row is an image row, and sample b's slot p holds the image that
+    the token map puts there."""
+    w = wl.scaled(wl.colocated4_dense(), 4)
+    tm = w.maps[0]
+    assert tm.n_rows == tm.batch * tm.seq
+    assert any(np.any(np.diff(tm.img_start[tm.img_sample == b]) < 0) for b in range(4))   # really out of order
+    X = (np.arange(tm.n_rows, dtype=np.uint32)[:, None] * 4 + np.arange(4)[None, :]).astype(np.uint32)
+    prob = oracle.Problem(w.src, w.dst, tm)
+    srcs = brute_sources(w.src, tm, X)
+    dsts = [np.full((prob.dst_rows(), 4), 0xFFFFFFFF, np.uint32) for _ in range(prob.n_dst)]
+    prob.forward(srcs, dsts)
+    want, is_img = brute_forward(w.src, w.dst, tm, X, 0xFFFFFFFF)
+    for j in range(prob.n_dst):
+        assert np.array_equal(dsts[j], want[j])
+        assert is_img[j].all()
+    # closed form: image k = 8 b + i sits at slot start/1024 of sample b
+    d0 = dsts[0].reshape(4, 8, 1024, 4)
+    for k in range(32):
+        b, slot = int(tm.img_sample[k]), int(tm.img_start[k]) // 1024
+        assert np.array_equal(d0[b, slot], X[1024 * k:1024 * (k + 1)])
+
+
+@pytest.mark.parametrize("seed", range(20))
 def test_forward_matches_global_slicing_seq_sharded(seed):
     rng = np.random.default_rng(5000 + seed)
     src, dst, tm = wl.random_layout_case(rng)

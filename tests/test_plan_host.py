@@ -72,7 +72,24 @@ def test_segments_match_oracle_walk_random_layouts(seed):
         check_against_oracle(src, replace(dst, tp_mode=wl.TP_SEQ_SHARD), tm)
 
 
-@pytest.mark.parametrize("name", ["tiny", "colocated4", "long_context", "large_scale"])
+@pytest.mark.parametrize("seed", range(20))
+def test_segments_match_oracle_walk_spans_out_of_position_order(seed):
+    rng = np.random.default_rng(300 + seed)
+    src, dst, tm = wl.random_layout_case(rng)
+    check_against_oracle(src, dst, wl.shuffle_spans(rng, tm))
+
+
+@pytest.mark.parametrize("k", [1, 2, 7, 8, 9, 32])
+def test_segments_match_oracle_walk_long_context_image_counts(k):
+    """Fewer images than source ranks (empty ranks), exactly as many, one more,
+    and the maximum of the long-context generator."""
+    w = wl.scaled(wl.long_context(n_images=k), 8)
+    info = check_against_oracle(w.src, w.dst, w.maps[0])
+    assert sum(1 for r in hp.hp_plan_create_host(w.src, w.dst, w.maps[0]).src_rows() if r == 0) == max(0, 8 - k)
+    assert 1 <= info.n_segments <= 3 * k
+
+
+@pytest.mark.parametrize("name", ["tiny", "colocated4", "colocated4_dense", "long_context", "large_scale"])
 def test_segments_match_oracle_walk_named_configs(name):
     w = wl.scaled(wl.CONFIGS[name](), 8)           # same spans and grids, small hidden
     info = check_against_oracle(w.src, w.dst, w.maps[0])
