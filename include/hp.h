@@ -129,16 +129,16 @@ typedef struct hp_token_map {
 typedef struct hp_plan hp_plan_t;
 
 typedef struct hp_plan_info {
-    int32_t n_src_bufs;        /* TP_src * DP_src                                             */
+    int32_t n_src_bufs;        /* TP_src * DP_src (times microbatches, summed over joined edges) */
     int32_t n_dst_bufs;        /* TP_dst * CP_dst * DP_dst                                    */
-    int32_t src_copies;        /* TP_src: identical copies of every source row                */
+    int32_t src_copies;        /* TP_src: identical copies of every source row (first edge)   */
     int32_t dst_copies;        /* TP_dst when replicated, 1 when sequence-sharded             */
     int64_t n_rows;            /* N: image-token rows of the boundary tensor                  */
     int64_t row_bytes;         /* hidden * element size                                       */
     int64_t dst_rows_per_buf;  /* rows of every destination buffer                            */
     int64_t boundary_bytes;    /* N * row_bytes                                               */
     int64_t fwd_bytes;         /* algorithmic traffic of hp_forward: (1 + dst_copies)*boundary */
-    int64_t bwd_bytes;         /* of hp_backward: (dst_copies + src_copies)*boundary          */
+    int64_t bwd_bytes;         /* of hp_backward: (dst_copies + src_copies)*boundary, per edge */
     int32_t n_segments;        /* runs contiguous on both sides                               */
     int32_t n_tiles;           /* workgroups of an hp_forward launch in its current shape     */
     int32_t on_device;         /* 1 if device tables exist                                    */
@@ -147,6 +147,8 @@ typedef struct hp_plan_info {
     int32_t elem_bytes;        /* 2 for HP_BF16, 4 for HP_F32                                 */
     int64_t bwd_accum_bytes;   /* algorithmic traffic of hp_backward_accumulate: dst_copies *
                                   boundary read + src_copies * N * hidden * 4 read and written */
+    int32_t n_edges;           /* source modules joined into the destination (1 unless joined) */
+    int32_t reserved;
 } hp_plan_info_t;
 
 /* A maximal run of image-token rows that is contiguous in the source buffer and
@@ -188,6 +190,26 @@ int hp_plan_create_host(const hp_layout_t *src, const hp_layout_t *dst,
 int hp_plan_create_batched(const hp_layout_t *src, const hp_layout_t *dst,
                            const hp_token_map_t *maps, int32_t n_maps,
                            int32_t host_only, hp_plan_t **out);
+
+/* One plan for a graph join: n_edges source modules (several encoders), each
+ * with its own grid srcs[e], feed the same destination module, and every edge
+ * is a boundary transform of its own into the one fused sequence ("Pipeline
+ * schedule details": the first LLM stage consumes several encoder activations
+ * for the same microbatch, and backward routes each gradient through the
+ * communicator of the edge it came in by).  maps[e * n_maps + m] is edge e's
+ * token map for microbatch m: where THAT encoder's tokens sit in the sequence.
+ * All maps share batch, seq, hidden and dtype; spans of different edges must
+ * not overlap (HP_EMAP).  One hp_forward launch scatters the tokens of every
+ * edge; one hp_backward launch returns each row's gradient to its own edge's
+ * source ranks, to all TP copies of that edge's grid.
+ * Source buffers are listed edge by edge: edge e starts at
+ * sum over e' < e of n_maps * TP_e' * DP_e', and inside the edge the index is
+ * m * (TP_e * DP_e) + tp + TP_e * dp.  Destination buffers as for
+ * hp_plan_create_batched, shared by all edges.  With n_edges = 1 this is
+ * hp_plan_create_batched. */
+int hp_plan_create_joined(const hp_layout_t *srcs, int32_t n_edges, const hp_layout_t *dst,
+                          const hp_token_map_t *maps, int32_t n_maps,
+                          int32_t host_only, hp_plan_t **out);
 
 /* Frees the host tables and hands the device block (a few KB) back to a small
  * per-process cache from which later hp_plan_create calls on the same device

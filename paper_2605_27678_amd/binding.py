@@ -51,7 +51,8 @@ class hp_plan_info_t(C.Structure):
                 ("boundary_bytes", C.c_int64), ("fwd_bytes", C.c_int64), ("bwd_bytes", C.c_int64),
                 ("n_segments", C.c_int32), ("n_tiles", C.c_int32),
                 ("on_device", C.c_int32), ("device", C.c_int32), ("n_maps", C.c_int32),
-                ("elem_bytes", C.c_int32), ("bwd_accum_bytes", C.c_int64)]
+                ("elem_bytes", C.c_int32), ("bwd_accum_bytes", C.c_int64),
+                ("n_edges", C.c_int32), ("reserved", C.c_int32)]
 
 
 class hp_segment_t(C.Structure):
@@ -64,7 +65,8 @@ class hp_launch_t(C.Structure):
                 ("waves_per_cu", C.c_int32), ("nontemporal", C.c_int32)]
 
 
-EXPORTS = ["hp_plan_create", "hp_plan_create_host", "hp_plan_create_batched", "hp_plan_destroy",
+EXPORTS = ["hp_plan_create", "hp_plan_create_host", "hp_plan_create_batched", "hp_plan_create_joined",
+           "hp_plan_destroy",
            "hp_release_cached_memory", "hp_forget_tuned_shapes",
            "hp_plan_query", "hp_plan_src_rows", "hp_plan_segments", "hp_plan_get_launch",
            "hp_plan_set_launch", "hp_plan_tune", "hp_plan_tune_accumulate", "hp_forward", "hp_backward", "hp_backward_accumulate",
@@ -90,6 +92,9 @@ def _lib():
     L.hp_plan_create_host.argtypes = L.hp_plan_create.argtypes
     L.hp_plan_create_batched.argtypes = [C.POINTER(hp_layout_t), C.POINTER(hp_layout_t),
                                          C.POINTER(hp_token_map_t), i32, i32, C.POINTER(vp)]
+    L.hp_plan_create_joined.argtypes = [C.POINTER(hp_layout_t), i32, C.POINTER(hp_layout_t),
+                                        C.POINTER(hp_token_map_t), i32, i32, C.POINTER(vp)]
+    L.hp_plan_create_joined.restype = C.c_int
     L.hp_plan_get_launch.argtypes = [vp, i32, C.POINTER(hp_launch_t)]
     L.hp_plan_set_launch.argtypes = [vp, i32, C.POINTER(hp_launch_t)]
     L.hp_plan_tune.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), C.POINTER(vp), vp]
@@ -203,10 +208,22 @@ class Plan:
     """Owns one hp_plan_t.  `host_only=True` builds the tables without touching
     the GPU (for inspection on machines without one)."""
 
-    def __init__(self, src: Grid, dst: Grid, tmap, host_only: bool = False):
+    def __init__(self, src, dst: Grid, tmap, host_only: bool = False):
         L = _lib()
         self._h = C.c_void_p(0)
-        if isinstance(tmap, TokenMap):
+        if not isinstance(src, Grid):           # several source grids: tmap[e][m] = edge e, microbatch m
+            srcs = list(src)
+            if len(tmap) != len(srcs) or any(len(row) != len(tmap[0]) for row in tmap) or not tmap[0]:
+                raise ValueError("joined plan: need one list of microbatch token maps per source grid, equally long")
+            pairs = [_token_map(m) for row in tmap for m in row]
+            arr = (hp_token_map_t * len(pairs))(*[p[0] for p in pairs])
+            keep = [p[1] for p in pairs]
+            layouts = (hp_layout_t * len(srcs))(*[_layout(g) for g in srcs])
+            _check(L.hp_plan_create_joined(layouts, len(srcs), C.byref(_layout(dst)), arr, len(tmap[0]),
+                                           1 if host_only else 0, C.byref(self._h)),
+                   "hp_plan_create_joined")
+            self.hidden = tmap[0][0].hidden
+        elif isinstance(tmap, TokenMap):
             tm, keep = _token_map(tmap)
             fn = L.hp_plan_create_host if host_only else L.hp_plan_create
             _check(fn(C.byref(_layout(src)), C.byref(_layout(dst)), C.byref(tm), C.byref(self._h)),
@@ -339,6 +356,12 @@ def hp_plan_create_host(src: Grid, dst: Grid, tmap: TokenMap) -> Plan:
 
 def hp_plan_create_batched(src: Grid, dst: Grid, tmaps: Sequence[TokenMap], host_only: bool = False) -> Plan:
     return Plan(src, dst, list(tmaps), host_only=host_only)
+
+
+def hp_plan_create_joined(srcs: Sequence[Grid], dst: Grid, tmaps: Sequence[Sequence[TokenMap]],
+                          host_only: bool = False) -> Plan:
+    """tmaps[e][m]: token map of edge e (source grid srcs[e]) for microbatch m."""
+    return Plan(list(srcs), dst, [list(row) for row in tmaps], host_only=host_only)
 
 
 def hp_plan_tune(plan: Plan, src_bufs=None, dst_bufs=None, dst_grad_bufs=None, src_grad_bufs=None,

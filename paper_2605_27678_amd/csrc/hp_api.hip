@@ -51,7 +51,6 @@ struct KParams {
     uint32_t rows_per_tile;     // for row-strided segments: max(1, tile_bytes / row_bytes)
     uint32_t dst_base;          // index of the first destination pointer in BufTable
     uint32_t dst_copies;        // replicas of each row on the destination side
-    uint32_t src_copies;        // identical copies on the source side
 };
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -74,6 +73,7 @@ struct TileView {
     uint32_t nbytes;
     uint32_t pitch_rows;        // 1 = dense destination
     uint32_t src_buf, dst_buf0;
+    uint32_t src_copies;        // identical TP copies of the source rank
 };
 
 // One node of the search tree: 16 ascending keys (padding = UINT32_MAX) fetched
@@ -111,6 +111,7 @@ __device__ __forceinline__ TileView locate_tile(const KParams &k, uint32_t tile)
     v.pitch_rows = s.pitch_rows;
     v.src_buf = s.src_buf;
     v.dst_buf0 = s.dst_buf0;
+    v.src_copies = s.src_copies;
     if (s.pitch_rows == 1) {
         const uint64_t off = (uint64_t)t * k.tile_bytes;
         const uint64_t left = (uint64_t)s.n_rows * k.row_bytes - off;
@@ -319,14 +320,14 @@ __device__ __forceinline__ void backward_group(const BufTable &bufs, const KPara
         VO res[U];
 #pragma unroll
         for (int u = 0; u < U; ++u) res[u] = Out::pack(acc[u]);
-        for (uint32_t s = 0; s < k.src_copies; ++s) {
+        for (uint32_t s = 0; s < t.src_copies; ++s) {
             char *out = (char *)bufs.p[t.src_buf + s] + out_off;
 #pragma unroll
             for (int u = 0; u < U; ++u)
                 if (!GUARD || i[u] < n) st<VO, NTS>((VO *)out + i[u], res[u]);
         }
     } else {
-        for (uint32_t s = 0; s < k.src_copies; ++s) {
+        for (uint32_t s = 0; s < t.src_copies; ++s) {
             char *out = (char *)bufs.p[t.src_buf + s] + out_off;
             VO old[U];
 #pragma unroll
@@ -551,7 +552,6 @@ int enqueue(const hp_plan *p, Direction dir, const hp::Launch &L, const BufTable
     k.rows_per_tile = std::max<uint32_t>(1u, k.tile_bytes / k.row_bytes);
     k.dst_base = (uint32_t)p->n_src_bufs;
     k.dst_copies = (uint32_t)p->dst_copies;
-    k.src_copies = (uint32_t)p->src_copies;
     LaunchCfg c;
     c.grid = dim3(p->n_tiles(L.tile_variant));
     c.block = dim3((unsigned)L.block);
@@ -599,7 +599,7 @@ int prepare(const hp_plan *p, Direction dir, const void *const *src, const void 
     int n = 0;
     uint64_t src_bits = 0, dst_bits = (uint64_t)p->row_bytes;
     for (int i = 0; i < p->n_src_bufs; ++i) {
-        const bool needed = p->src_rows[i] > 0 && (dir != kForward || i % p->src_copies == 0);
+        const bool needed = p->src_rows[i] > 0 && (dir != kForward || p->src_leader[i]);
         if (needed && !src[i]) return HP_EINVAL;
         bt->p[n++] = needed ? const_cast<void *>(src[i]) : nullptr;
         if (needed) src_bits |= (uint64_t)(uintptr_t)src[i];
@@ -770,14 +770,14 @@ struct ShapeCache {
     }
 } g_shapes;
 
-int create_common(const hp_layout_t *src, const hp_layout_t *dst, const hp_token_map_t *maps,
+int create_common(const hp_layout_t *srcs, int32_t n_edges, const hp_layout_t *dst, const hp_token_map_t *maps,
                   int32_t n_maps, bool upload, hp_plan_t **out) {
     if (!out) return HP_EINVAL;
     hp_plan *p = new (std::nothrow) hp_plan();
     if (!p) return HP_ENOMEM;
     int rc;
     try {
-        rc = hp::build_host_plan(src, dst, maps, n_maps, p);
+        rc = hp::build_host_plan(srcs, n_edges, dst, maps, n_maps, p);
     } catch (const std::bad_alloc &) {
         rc = HP_ENOMEM;
     } catch (...) {
@@ -999,17 +999,22 @@ extern "C" {
 
 int hp_plan_create(const hp_layout_t *src, const hp_layout_t *dst, const hp_token_map_t *map,
                    hp_plan_t **out) {
-    return create_common(src, dst, map, 1, true, out);
+    return create_common(src, 1, dst, map, 1, true, out);
 }
 
 int hp_plan_create_host(const hp_layout_t *src, const hp_layout_t *dst, const hp_token_map_t *map,
                         hp_plan_t **out) {
-    return create_common(src, dst, map, 1, false, out);
+    return create_common(src, 1, dst, map, 1, false, out);
 }
 
 int hp_plan_create_batched(const hp_layout_t *src, const hp_layout_t *dst, const hp_token_map_t *maps,
                            int32_t n_maps, int32_t host_only, hp_plan_t **out) {
-    return create_common(src, dst, maps, n_maps, host_only == 0, out);
+    return create_common(src, 1, dst, maps, n_maps, host_only == 0, out);
+}
+
+int hp_plan_create_joined(const hp_layout_t *srcs, int32_t n_edges, const hp_layout_t *dst,
+                          const hp_token_map_t *maps, int32_t n_maps, int32_t host_only, hp_plan_t **out) {
+    return create_common(srcs, n_edges, dst, maps, n_maps, host_only == 0, out);
 }
 
 void hp_plan_destroy(hp_plan_t *plan) {
@@ -1035,15 +1040,15 @@ int hp_plan_query(const hp_plan_t *p, hp_plan_info_t *info) {
     o.dst_rows_per_buf = p->dst_rows_per_buf;
     o.boundary_bytes = p->n_rows * p->row_bytes;
     o.fwd_bytes = (1 + (int64_t)p->dst_copies) * o.boundary_bytes;
-    o.bwd_bytes = ((int64_t)p->dst_copies + p->src_copies) * o.boundary_bytes;
+    o.bwd_bytes = p->bwd_bytes;
     o.n_segments = (int32_t)p->segments.size();
     o.n_tiles = (int32_t)p->n_tiles(p->fwd.tile_variant);
     o.on_device = (p->d_segs != nullptr || (p->device >= 0 && p->segments.empty())) ? 1 : 0;
     o.device = p->device;
     o.n_maps = p->n_maps;
     o.elem_bytes = p->elem_bytes;
-    o.bwd_accum_bytes = (int64_t)p->dst_copies * o.boundary_bytes +
-                        (int64_t)p->src_copies * 2 * p->n_rows * p->hidden * 4;
+    o.bwd_accum_bytes = p->bwd_accum_bytes;
+    o.n_edges = p->n_edges;
     *info = o;
     return HP_OK;
 }

@@ -81,7 +81,7 @@ struct DstWalker {
     }
 };
 
-int validate(const hp_layout_t *src, const hp_layout_t *dst, const hp_token_map_t *m, int32_t n_maps) {
+int validate(const hp_layout_t *src, const hp_layout_t *dst, const hp_token_map_t *m) {
     if (!src || !dst || !m) return HP_EINVAL;
     for (const hp_layout_t *g : {src, dst}) {
         if (g->tp < 1 || g->cp < 1 || g->dp < 1 || g->pp < 1 || g->rank_offset < 0) return HP_EINVAL;
@@ -99,9 +99,7 @@ int validate(const hp_layout_t *src, const hp_layout_t *dst, const hp_token_map_
     if (m->seq % dst->cp) return HP_ELAYOUT;
     if (dst->cp_split == HP_CP_ZIGZAG && m->seq % (2 * (int64_t)dst->cp)) return HP_ELAYOUT;
     if (dst->tp_mode == HP_TP_SEQ_SHARD && (m->seq / dst->cp) % dst->tp) return HP_ELAYOUT;
-    int64_t n_src = (int64_t)src->tp * src->dp;
-    int64_t n_dst = (int64_t)dst->tp * dst->cp * dst->dp;
-    if ((n_src + n_dst) * n_maps > HP_MAX_BUFFERS) return HP_ELAYOUT;
+    if ((int64_t)src->tp * src->dp + (int64_t)dst->tp * dst->cp * dst->dp > HP_MAX_BUFFERS) return HP_ELAYOUT;
     if (dst->tp_mode == HP_TP_REPLICATE && dst->tp > HP_MAX_TP) return HP_ELAYOUT;
 
     // spans
@@ -151,7 +149,7 @@ int make_tables(hp_plan *p) {
         d.src_off = (uint64_t)s.src_row0 * p->row_bytes;
         d.dst_off = (uint64_t)s.dst_row0 * p->row_bytes;
         d.n_rows = (uint32_t)s.n_rows;
-        d.reserved = 0;
+        d.src_copies = (uint32_t)p->seg_copies[i];
         d.pitch_rows = (uint32_t)s.dst_row_stride;
         d.src_buf = (uint16_t)s.src_buf;
         d.dst_buf0 = (uint16_t)s.dst_buf0;
@@ -192,33 +190,63 @@ int make_tables(hp_plan *p) {
     return HP_OK;
 }
 
+// No two spans of one microbatch may overlap, whichever edge they belong to.
+int check_cross_edge_overlap(const hp_token_map_t *maps, int32_t n_edges, int32_t n_maps) {
+    struct Span { int32_t b; int64_t s, e; };
+    std::vector<Span> spans;
+    for (int32_t mi = 0; mi < n_maps; ++mi) {
+        spans.clear();
+        for (int32_t e = 0; e < n_edges; ++e) {
+            const hp_token_map_t &m = maps[(size_t)e * n_maps + mi];
+            for (int32_t k = 0; k < m.n_images; ++k)
+                spans.push_back(Span{m.img_sample[k], m.img_start[k], (int64_t)m.img_start[k] + m.img_len[k]});
+        }
+        std::sort(spans.begin(), spans.end(), [](const Span &x, const Span &y) {
+            return x.b != y.b ? x.b < y.b : x.s < y.s;
+        });
+        for (size_t i = 1; i < spans.size(); ++i)
+            if (spans[i].b == spans[i - 1].b && spans[i].s < spans[i - 1].e) return HP_EMAP;
+    }
+    return HP_OK;
+}
+
 }  // namespace
 
-int build_host_plan(const hp_layout_t *src, const hp_layout_t *dst,
+int build_host_plan(const hp_layout_t *srcs, int32_t n_edges, const hp_layout_t *dst,
                     const hp_token_map_t *maps, int32_t n_maps, hp_plan *p) {
-    if (!maps || n_maps < 1) return HP_EINVAL;
-    for (int32_t i = 0; i < n_maps; ++i) {
-        int rc = validate(src, dst, &maps[i], n_maps);
+    if (!srcs || !maps || n_maps < 1 || n_edges < 1) return HP_EINVAL;
+    int64_t n_bufs = 0;
+    for (int32_t e = 0; e < n_edges; ++e) {
+        for (int32_t i = 0; i < n_maps; ++i) {
+            const hp_token_map_t &m = maps[(size_t)e * n_maps + i];
+            int rc = validate(&srcs[e], dst, &m);
+            if (rc != HP_OK) return rc;
+            // microbatches and edges share the buffer shapes
+            if (m.batch != maps[0].batch || m.seq != maps[0].seq || m.hidden != maps[0].hidden ||
+                m.dtype != maps[0].dtype)
+                return HP_ELAYOUT;
+        }
+        n_bufs += (int64_t)srcs[e].tp * srcs[e].dp * n_maps;
+    }
+    n_bufs += (int64_t)dst->tp * dst->cp * dst->dp * n_maps;
+    if (n_bufs > HP_MAX_BUFFERS) return HP_ELAYOUT;
+    if (n_edges > 1) {
+        int rc = check_cross_edge_overlap(maps, n_edges, n_maps);
         if (rc != HP_OK) return rc;
-        // microbatches share the buffer shapes
-        if (maps[i].batch != maps[0].batch || maps[i].seq != maps[0].seq ||
-            maps[i].hidden != maps[0].hidden || maps[i].dtype != maps[0].dtype)
-            return HP_ELAYOUT;
     }
     const hp_token_map_t *m0 = &maps[0];
 
-    p->src = *src;
+    p->src = srcs[0];
     p->dst = *dst;
     p->batch = m0->batch; p->seq = m0->seq; p->hidden = m0->hidden; p->dtype = m0->dtype;
     p->n_maps = n_maps;
+    p->n_edges = n_edges;
     p->elem_bytes = m0->dtype == HP_F32 ? 4 : 2;
     p->row_bytes = (int64_t)m0->hidden * p->elem_bytes;
     if (p->row_bytes > (int64_t)1 << 24) return HP_ELAYOUT;       // a tile holds whole rows in 32 bits
-    const int32_t src_per_map = src->tp * src->dp;
     const int32_t dst_per_map = dst->tp * dst->cp * dst->dp;
-    p->n_src_bufs = src_per_map * n_maps;
     p->n_dst_bufs = dst_per_map * n_maps;
-    p->src_copies = src->tp;
+    p->src_copies = srcs[0].tp;
     p->dst_copies = dst->tp_mode == HP_TP_SEQ_SHARD ? 1 : dst->tp;
 
     const DstWalker walk(*dst, m0->seq);
@@ -228,56 +256,79 @@ int build_host_plan(const hp_layout_t *src, const hp_layout_t *dst,
     const int64_t stride = (sbh && b_loc > 1) ? b_loc : 1;
 
     p->n_rows = 0;
+    p->bwd_bytes = p->bwd_accum_bytes = 0;
     p->segments.clear();
-    p->src_rows.assign(p->n_src_bufs, 0);
-    for (int32_t mi = 0; mi < n_maps; ++mi) {
-        const hp_token_map_t *m = &maps[mi];
-        const int32_t src_base = mi * src_per_map, dst_base = mi * dst_per_map;
-        // source side: each dp rank's buffer fills up in global image order
-        std::vector<int64_t> fill(src->dp, 0);
-        const int64_t K = m->n_images;
-        int32_t d = 0;
-        for (int64_t k = 0; k < K; ++k) {
-            if (m->img_src_dp) {
-                d = m->img_src_dp[k];
-            } else {
-                while (k >= ((int64_t)(d + 1) * K) / src->dp) ++d;    // next balanced interval
-            }
-            const int32_t b = m->img_sample[k];
-            const int32_t dpd = (int32_t)(b / b_loc);
-            const int64_t bl = b - (int64_t)dpd * b_loc;
-            int64_t s = m->img_start[k], left = m->img_len[k];
-            while (left > 0) {
-                const DstPos pos = walk.at(dpd, s);
-                const int64_t n = std::min(left, pos.run);
-                hp_segment_t seg;
-                seg.src_buf = src_base + d * src->tp;
-                seg.dst_buf0 = dst_base + pos.buf0;
-                seg.src_row0 = fill[d];
-                seg.dst_row0 = sbh ? pos.s_loc * b_loc + bl : bl * walk.piece + pos.s_loc;
-                seg.n_rows = n;
-                seg.dst_row_stride = stride;
-                bool merged = false;
-                if (!p->segments.empty()) {
-                    hp_segment_t &q = p->segments.back();
-                    if (q.src_buf == seg.src_buf && q.dst_buf0 == seg.dst_buf0 &&
-                        q.dst_row_stride == seg.dst_row_stride &&
-                        q.src_row0 + q.n_rows == seg.src_row0 &&
-                        q.dst_row0 + q.n_rows * q.dst_row_stride == seg.dst_row0) {
-                        q.n_rows += n;
-                        merged = true;
-                    }
+    p->seg_copies.clear();
+    p->src_rows.clear();
+    p->src_leader.clear();
+    int32_t edge_base = 0;
+    for (int32_t e = 0; e < n_edges; ++e) {
+        const hp_layout_t *src = &srcs[e];
+        const int32_t src_per_map = src->tp * src->dp;
+        p->src_rows.resize((size_t)edge_base + (size_t)src_per_map * n_maps, 0);
+        p->src_leader.resize(p->src_rows.size(), 0);
+        int64_t edge_rows = 0;
+        for (int32_t mi = 0; mi < n_maps; ++mi) {
+            const hp_token_map_t *m = &maps[(size_t)e * n_maps + mi];
+            const int32_t src_base = edge_base + mi * src_per_map, dst_base = mi * dst_per_map;
+            // source side: each dp rank's buffer fills up in global image order
+            std::vector<int64_t> fill(src->dp, 0);
+            const int64_t K = m->n_images;
+            int32_t d = 0;
+            for (int64_t k = 0; k < K; ++k) {
+                if (m->img_src_dp) {
+                    d = m->img_src_dp[k];
+                } else {
+                    while (k >= ((int64_t)(d + 1) * K) / src->dp) ++d;    // next balanced interval
                 }
-                if (!merged) p->segments.push_back(seg);
-                fill[d] += n;
-                p->n_rows += n;
-                s += n;
-                left -= n;
+                const int32_t b = m->img_sample[k];
+                const int32_t dpd = (int32_t)(b / b_loc);
+                const int64_t bl = b - (int64_t)dpd * b_loc;
+                int64_t s = m->img_start[k], left = m->img_len[k];
+                while (left > 0) {
+                    const DstPos pos = walk.at(dpd, s);
+                    const int64_t n = std::min(left, pos.run);
+                    hp_segment_t seg;
+                    seg.src_buf = src_base + d * src->tp;
+                    seg.dst_buf0 = dst_base + pos.buf0;
+                    seg.src_row0 = fill[d];
+                    seg.dst_row0 = sbh ? pos.s_loc * b_loc + bl : bl * walk.piece + pos.s_loc;
+                    seg.n_rows = n;
+                    seg.dst_row_stride = stride;
+                    bool merged = false;
+                    if (!p->segments.empty()) {
+                        hp_segment_t &q = p->segments.back();
+                        if (q.src_buf == seg.src_buf && q.dst_buf0 == seg.dst_buf0 &&
+                            q.dst_row_stride == seg.dst_row_stride &&
+                            q.src_row0 + q.n_rows == seg.src_row0 &&
+                            q.dst_row0 + q.n_rows * q.dst_row_stride == seg.dst_row0) {
+                            q.n_rows += n;
+                            merged = true;
+                        }
+                    }
+                    if (!merged) {
+                        p->segments.push_back(seg);
+                        p->seg_copies.push_back(src->tp);
+                    }
+                    fill[d] += n;
+                    edge_rows += n;
+                    s += n;
+                    left -= n;
+                }
             }
+            for (int32_t dd = 0; dd < src->dp; ++dd)
+                for (int32_t t = 0; t < src->tp; ++t) {
+                    p->src_rows[src_base + t + src->tp * dd] = fill[dd];
+                    p->src_leader[src_base + t + src->tp * dd] = t == 0;
+                }
         }
-        for (int32_t dd = 0; dd < src->dp; ++dd)
-            for (int32_t t = 0; t < src->tp; ++t) p->src_rows[src_base + t + src->tp * dd] = fill[dd];
+        p->n_rows += edge_rows;
+        const int64_t edge_bytes = edge_rows * p->row_bytes;
+        p->bwd_bytes += ((int64_t)p->dst_copies + src->tp) * edge_bytes;
+        p->bwd_accum_bytes += (int64_t)p->dst_copies * edge_bytes + (int64_t)src->tp * 2 * edge_rows * p->hidden * 4;
+        edge_base += src_per_map * n_maps;
     }
+    p->n_src_bufs = edge_base;
 
     const Options &o = options();
     p->fwd = Launch{tile_variant_of(o.tile_bytes_fwd), (int32_t)o.block_threads_fwd,

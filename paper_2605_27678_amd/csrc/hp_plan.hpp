@@ -19,7 +19,7 @@ struct alignas(16) Seg {
     uint32_t pitch_rows;  // destination row pitch in rows (1 = dense)
     uint16_t src_buf;     // source buffer index of copy tp = 0
     uint16_t dst_buf0;    // first destination buffer index
-    uint32_t reserved;
+    uint32_t src_copies;  // identical TP copies of the source rank (buffers src_buf .. +src_copies-1)
 };
 static_assert(sizeof(Seg) == 32, "segment descriptor must stay 32 bytes");
 
@@ -67,13 +67,17 @@ struct hp_plan {
     hp_layout_t src{}, dst{};
     int32_t batch = 0, seq = 0, hidden = 0, dtype = 0;
     int32_t n_maps = 1;                   // microbatches folded into this plan
+    int32_t n_edges = 1;                  // source modules joined into the one destination
     int32_t elem_bytes = 2;
     int64_t row_bytes = 0;
     int64_t n_rows = 0;
     int32_t n_src_bufs = 0, n_dst_bufs = 0;   // totals over all microbatches
-    int32_t src_copies = 1, dst_copies = 1;
+    int32_t src_copies = 1, dst_copies = 1;   // src_copies: of the first edge (edges may differ, see seg_copies)
+    int64_t bwd_bytes = 0, bwd_accum_bytes = 0;   // algorithmic bytes of the two backward flavours
     int64_t dst_rows_per_buf = 0;
     std::vector<int64_t> src_rows;        // per source buffer
+    std::vector<uint8_t> src_leader;      // per source buffer: 1 = copy tp 0 of its rank (the one forward reads)
+    std::vector<int32_t> seg_copies;      // per segment: TP copies of its source rank
     std::vector<hp_segment_t> segments;   // public view (rows)
     std::vector<hp::Seg> dsegs;           // device view (bytes)
     std::vector<uint32_t> first_tile;     // kTileVariants x (n_segments + 1), row-major
@@ -104,10 +108,13 @@ struct hp_plan {
 };
 
 namespace hp {
-// Validates and fills everything except the device fields for `n_maps` token
-// maps that share the two grids (buffers of microbatch m follow those of
-// microbatch m-1 on both sides).  Returns HP_OK or a negative error; *plan is
-// only meaningful on HP_OK.
-int build_host_plan(const hp_layout_t *src, const hp_layout_t *dst,
+// Validates and fills everything except the device fields for `n_edges` source
+// modules that feed one destination module, each with `n_maps` token maps
+// (maps[e * n_maps + m] = edge e, microbatch m; all share batch, sequence length,
+// hidden size and dtype, and the spans of different edges must not overlap).
+// Source buffers are listed edge by edge, inside an edge microbatch by
+// microbatch; destination buffers microbatch by microbatch, shared by all
+// edges.  Returns HP_OK or a negative error; *plan is only meaningful on HP_OK.
+int build_host_plan(const hp_layout_t *srcs, int32_t n_edges, const hp_layout_t *dst,
                     const hp_token_map_t *maps, int32_t n_maps, hp_plan *plan);
 }  // namespace hp

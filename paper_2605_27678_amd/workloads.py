@@ -161,6 +161,19 @@ def shuffle_spans(rng: np.random.Generator, tm: TokenMap) -> TokenMap:
     return replace(tm, img_start=start.astype(np.int32), img_len=length.astype(np.int32))
 
 
+def split_edges(rng: np.random.Generator, tm: TokenMap, n_edges: int) -> List[TokenMap]:
+    """Deals the spans of one token map out to n_edges encoders at random (a
+    graph join: several encoders feed disjoint spans of the same sequence).
+    Every returned map keeps the sample-major order; an edge may get no span."""
+    owner = rng.integers(0, n_edges, size=tm.n_images)
+    out = []
+    for e in range(n_edges):
+        sel = owner == e
+        out.append(TokenMap(tm.batch, tm.seq, tm.hidden, tm.img_sample[sel], tm.img_start[sel],
+                            tm.img_len[sel], None, tm.dtype))
+    return out
+
+
 def colocated4_dense(seed: int = BASE_SEED + 2) -> Workload:
     """Config 2 under its other reading: the stated sequence length of 8192 is
     the fused length, so the 8 images x 1024 tokens of a sample tile the whole

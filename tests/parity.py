@@ -40,11 +40,14 @@ def make_inputs(prob: oracle.Problem, seed: int, gen_device: str):
 
 
 def check_case(src_grid, dst_grid, tm, seed=1, gen_device="cpu", stream=None, check_backward=True,
-               grads_override=None):
+               grads_override=None, expect_launch=None):
     """Runs forward and backward on both sides and asserts bit equality.
-    Returns the plan info."""
+    Returns the plan info.  expect_launch: the (forward, backward) launch
+    shapes the new plan must start from."""
     dev = "cuda:0"
     plan = hp.hp_plan_create(src_grid, dst_grid, tm)
+    if expect_launch is not None:
+        assert (plan.get_launch(0), plan.get_launch(1)) == expect_launch
     prob = oracle.Problem(src_grid, dst_grid, tm)
     assert plan.src_rows() == prob.src_rows()
     assert plan.info.dst_rows_per_buf == prob.dst_rows()

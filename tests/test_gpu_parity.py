@@ -267,6 +267,24 @@ def test_full_long_context():
     assert info.dst_copies == 4 and info.row_bytes == 10240
 
 
+def test_full_long_context_in_tuned_launch_shapes():
+    """The benchmark's configuration: hp_plan_tune first, then the full-size
+    comparison on a plan that starts from the remembered shapes."""
+    w = wl.long_context()
+    tm = w.maps[0]
+    plan = hp.hp_plan_create(w.src, w.dst, tm)
+    rows, drows, H = plan.src_rows(), plan.info.dst_rows_per_buf, tm.hidden
+    src = [wl.random_bf16((r, H), 5 + i, "cuda") for i, r in enumerate(rows)]
+    dst = [torch.empty((drows, H), dtype=torch.bfloat16, device="cuda") for _ in range(32)]
+    grad = [wl.random_bf16((drows, H), 90 + j, "cuda") for j in range(32)]
+    sg = [torch.empty((r, H), dtype=torch.bfloat16, device="cuda") for r in rows]
+    hp.hp_plan_tune(plan, src, dst, grad, sg, torch.cuda.current_stream())
+    tuned = (plan.get_launch(0), plan.get_launch(1))
+    plan.close()
+    del src, dst, grad, sg
+    check_case(w.src, w.dst, tm, seed=33, gen_device="cuda", expect_launch=tuned)
+
+
 def test_full_non_colocated_microbatches():
     w = wl.non_colocated()
     for i in (0, 7, 15):
@@ -572,3 +590,63 @@ def test_plan_destroyed_while_its_calls_are_still_queued():
         for j in range(prob.n_dst):
             assert np.array_equal(_to_host_bits(got[j]), want[j]), j
     plan_b.close()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_joined_plan_one_launch_for_all_edges(seed):
+    """Two or three encoders with different grids (different TP widths, so the
+    backward writes a different number of copies per edge) join one sequence,
+    two microbatches: one hp_forward and one hp_backward launch for everything,
+    checked against the oracle applied edge by edge and microbatch by
+    microbatch.  Also the accumulating backward."""
+    rng = np.random.default_rng(900 + seed)
+    n_edges, n_maps = 2 + seed % 2, 2
+    B, S, H = 2, 512, (64, 40, 7)[seed % 3]
+    dst = wl.Grid(tp=(2, 3, 4)[seed % 3], cp=2, dp=1 + seed % 2, cp_split=wl.CP_ZIGZAG if seed % 2 else wl.CP_CONTIGUOUS)
+    srcs = [wl.Grid(tp=1 + (e + seed) % 2, dp=int(rng.choice([1, 2, 3, 4])), rank_offset=16 * e) for e in range(n_edges)]
+    maps = [[None] * n_maps for _ in range(n_edges)]
+    for m in range(n_maps):
+        lens = [[int(x) for x in rng.integers(1, 60, size=int(rng.integers(1, 6)))] for _ in range(B)]
+        tm = wl.token_map_from_lens(rng, B, S, H, lens)
+        for e, part in enumerate(wl.split_edges(rng, tm, n_edges)):
+            maps[e][m] = part
+    plan = hp.hp_plan_create_joined(srcs, dst, maps)
+    n_dst = dst.tp * dst.cp * dst.dp
+    drows = plan.info.dst_rows_per_buf
+    rows = plan.src_rows()
+    x = [wl.random_bf16((r, H), 1000 * seed + i) for i, r in enumerate(rows)]
+    pre = [wl.random_bf16((drows, H), 1000 * seed + 300 + j) for j in range(n_dst * n_maps)]
+    grads = [wl.random_bf16((drows, H), 1000 * seed + 600 + j) for j in range(n_dst * n_maps)]
+    acc0 = [torch.randn((r, H), generator=torch.Generator().manual_seed(seed * 31 + i)) for i, r in enumerate(rows)]
+    g_dst = [t.cuda() for t in pre]
+    g_sg = [torch.full((r, H), float("nan"), dtype=torch.bfloat16, device="cuda") for r in rows]
+    g_acc = [t.cuda() for t in acc0]
+    g_grads = [t.cuda() for t in grads]
+    hp.hp_forward(plan, [t.cuda() for t in x], g_dst)
+    hp.hp_backward(plan, g_grads, g_sg)
+    hp.hp_backward_accumulate(plan, g_grads, g_acc)
+    torch.cuda.synchronize()
+    # oracle, one (edge, microbatch) at a time
+    o_dst = [_to_host_bits(t).copy() for t in pre]
+    base = 0
+    for e in range(n_edges):
+        per_map = srcs[e].tp * srcs[e].dp
+        for m in range(n_maps):
+            prob = oracle.Problem(srcs[e], dst, maps[e][m])
+            sl = slice(base + m * per_map, base + (m + 1) * per_map)
+            dl = slice(m * n_dst, (m + 1) * n_dst)
+            assert rows[sl] == prob.src_rows()
+            prob.forward([_to_host_bits(t) for t in x[sl]], o_dst[dl])
+            hg = [_to_host_bits(t) for t in grads[dl]]
+            want = [np.zeros((r, H), np.uint16) for r in rows[sl]]
+            prob.backward_bf16(hg, want)
+            for a, b in zip(g_sg[sl], want):
+                assert np.array_equal(_to_host_bits(a), b), (e, m)
+            o_acc = [t.numpy().copy() for t in acc0[sl]]
+            prob.backward_accumulate(hg, o_acc)
+            for a, b in zip(g_acc[sl], o_acc):
+                assert np.array_equal(a.cpu().numpy().view(np.uint32), b.view(np.uint32)), (e, m)
+        base += per_map * n_maps
+    for j in range(n_dst * n_maps):
+        assert np.array_equal(_to_host_bits(g_dst[j]), o_dst[j]), j
+    plan.close()

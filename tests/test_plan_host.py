@@ -230,3 +230,88 @@ def test_launch_shape_get_set_and_tile_counts():
     assert q.info.n_tiles == sum(-(-s.n_rows // 3) for s in q.segments())
     L = binding._lib()
     assert L.hp_plan_tune(None, None, None, None, None, None) == binding.HP_EINVAL
+
+
+# ---- joined plans: several source modules into one destination -----------------
+
+def _joined_case(seed, n_edges=2, n_maps=2):
+    rng = np.random.default_rng(seed)
+    _, dst, tm0 = wl.random_layout_case(rng)
+    srcs = [wl.Grid(tp=int(rng.choice([1, 2])), dp=int(rng.choice([1, 2, 3, 4])), rank_offset=8 * e)
+            for e in range(n_edges)]
+    maps = [[None] * n_maps for _ in range(n_edges)]
+    for m in range(n_maps):
+        _, _, tm = wl.random_layout_case(rng)
+        # same shapes as microbatch 0, fresh spans
+        lens = [[int(x) for x in rng.integers(1, 6, size=int(rng.integers(0, 4)))] for _ in range(tm0.batch)]
+        lens = [l if sum(l) <= tm0.seq else [] for l in lens]
+        tm = wl.token_map_from_lens(rng, tm0.batch, tm0.seq, tm0.hidden, lens) if any(lens) else \
+            wl.TokenMap(tm0.batch, tm0.seq, tm0.hidden, [], [], [])
+        for e, part in enumerate(wl.split_edges(rng, tm, n_edges)):
+            maps[e][m] = part
+    return srcs, dst, maps
+
+
+@pytest.mark.parametrize("seed", range(30))
+def test_joined_plan_is_the_union_of_its_edges(seed):
+    """Segments, source rows and byte counts of a joined plan equal those of one
+    batched plan per edge, with the source buffers listed edge by edge; and the
+    row-by-row expansion equals the oracle's walk of every (edge, microbatch)."""
+    n_edges, n_maps = 2 + seed % 2, 1 + seed % 3
+    srcs, dst, maps = _joined_case(seed, n_edges, n_maps)
+    joined = hp.hp_plan_create_joined(srcs, dst, maps, host_only=True)
+    assert joined.info.n_edges == n_edges and joined.info.n_maps == n_maps
+    per_edge = [hp.hp_plan_create_batched(srcs[e], dst, maps[e], host_only=True) for e in range(n_edges)]
+    assert joined.src_rows() == [r for p in per_edge for r in p.src_rows()]
+    assert joined.info.n_rows == sum(p.info.n_rows for p in per_edge)
+    assert joined.info.fwd_bytes == sum(p.info.fwd_bytes for p in per_edge)
+    assert joined.info.bwd_bytes == sum(p.info.bwd_bytes for p in per_edge)
+    assert joined.info.bwd_accum_bytes == sum(p.info.bwd_accum_bytes for p in per_edge)
+    want, base = [], 0
+    for p in per_edge:
+        want += [(s.src_buf + base, s.dst_buf0, s.src_row0, s.dst_row0, s.n_rows, s.dst_row_stride)
+                 for s in p.segments()]
+        base += p.info.n_src_bufs
+    got = [(s.src_buf, s.dst_buf0, s.src_row0, s.dst_row0, s.n_rows, s.dst_row_stride) for s in joined.segments()]
+    assert got == want
+    # against the oracle: destination buffer j of microbatch m, as seen from every edge
+    sb, sr = expand_segments(joined)
+    n_dst = dst.tp * dst.cp * dst.dp
+    base = 0
+    seen = np.zeros_like(sb, dtype=bool)
+    for e in range(n_edges):
+        per_map = srcs[e].tp * srcs[e].dp
+        for m in range(n_maps):
+            prob = oracle.Problem(srcs[e], dst, maps[e][m])
+            for j in range(n_dst):
+                osb, osr = prob.forward_map(j)
+                rows = osb >= 0
+                assert np.array_equal(sb[m * n_dst + j][rows], osb[rows] + base + m * per_map)
+                assert np.array_equal(sr[m * n_dst + j][rows], osr[rows])
+                assert not seen[m * n_dst + j][rows].any()
+                seen[m * n_dst + j][rows] = True
+        base += per_map * n_maps
+    assert np.array_equal(seen, sb >= 0)             # nothing beyond what the edges account for
+
+
+def test_joined_plan_errors():
+    dst = wl.Grid(tp=2, cp=2, cp_split=wl.CP_ZIGZAG)
+    a = wl.TokenMap(1, 64, 8, [0, 0], [4, 30], [10, 6])
+    b_ok = wl.TokenMap(1, 64, 8, [0], [14], [16])
+    b_overlap = wl.TokenMap(1, 64, 8, [0], [13], [4])              # runs into a's first span
+    b_hidden = wl.TokenMap(1, 64, 16, [0], [14], [16])
+    srcs = [wl.Grid(dp=2), wl.Grid(tp=2, dp=1)]
+    hp.hp_plan_create_joined(srcs, dst, [[a], [b_ok]], host_only=True).close()
+    for maps, code in (([[a], [b_overlap]], binding.HP_EMAP), ([[a], [b_hidden]], binding.HP_ELAYOUT)):
+        with pytest.raises(hp.HpError) as ei:
+            hp.hp_plan_create_joined(srcs, dst, maps, host_only=True)
+        assert ei.value.code == code
+    with pytest.raises(ValueError):
+        hp.hp_plan_create_joined(srcs, dst, [[a]], host_only=True)
+    # too many buffers in total: 2 edges x dp 200 + 4 destination buffers
+    big = [wl.Grid(dp=222), wl.Grid(dp=222)]
+    empty = wl.TokenMap(1, 64, 8, [], [], [])
+    hp.hp_plan_create_joined(big, dst, [[a], [empty]], host_only=True).close()      # 444 + 4 = 448: allowed
+    with pytest.raises(hp.HpError) as ei:
+        hp.hp_plan_create_joined([wl.Grid(dp=223), wl.Grid(dp=222)], dst, [[a], [empty]], host_only=True)
+    assert ei.value.code == binding.HP_ELAYOUT
