@@ -61,6 +61,8 @@ def main() -> int:
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "f32"], help="payload element type")
     ap.add_argument("--seq-shard", action="store_true",
                     help="destination TP ranks hold sequence shards instead of replicas (sequence parallelism)")
+    ap.add_argument("--row-order", default="bsh", choices=["bsh", "sbh"],
+                    help="destination buffers as [B,S,H] or [S,B,H] (row-strided when a rank holds several samples)")
     ap.add_argument("--accumulate", action="store_true",
                     help="backward adds into fp32 source accumulators (hp_backward_accumulate)")
     ap.add_argument("--per-microbatch", action="store_true",
@@ -91,6 +93,8 @@ def main() -> int:
     w = wl.CONFIGS[args.workload]()
     if args.seq_shard:
         w = replace(w, dst=replace(w.dst, tp_mode=wl.TP_SEQ_SHARD))
+    if args.row_order == "sbh":
+        w = replace(w, dst=replace(w.dst, row_order=wl.ROW_SBH))
     if args.dtype == "f32":
         w = replace(w, maps=[replace(m, dtype=wl.DT_F32) for m in w.maps])
     tdtype = torch.float32 if args.dtype == "f32" else torch.bfloat16
@@ -314,7 +318,7 @@ def main() -> int:
         "config": {"workload": w.name, "src": f"tp{w.src.tp}dp{w.src.dp}",
                    "dst": f"tp{w.dst.tp}cp{w.dst.cp}dp{w.dst.dp}",
                    "batch": maps[0].batch, "seq": maps[0].seq, "hidden": H, "microbatches": len(maps),
-                   "tp_mode": "seq_shard" if args.seq_shard else "replicate",
+                   "tp_mode": "seq_shard" if args.seq_shard else "replicate", "row_order": args.row_order,
                    "backward": "accumulate_f32" if args.accumulate else "overwrite",
                    "accumulate_dtype": "f32", "launches_per_direction": n_launch, "launch_shapes": shapes, "tuned": not args.no_tune,
                    "submission": "hip_graph_replay" if args.graph else "eager",

@@ -48,7 +48,8 @@ struct KParams {
     uint32_t level_off[hp::kMaxTreeLevels];   // start of each level, in keys; level 0 = leaves
     uint32_t tile_bytes;
     uint32_t row_bytes;
-    uint32_t rows_per_tile;     // for row-strided segments: max(1, tile_bytes / row_bytes)
+    uint32_t rows_per_tile;     // row-strided segments, rows shorter than a tile: tile_bytes / row_bytes
+    uint32_t parts_per_row;     // row-strided segments, rows of at least a tile: ceil(row_bytes / tile_bytes); else 0
     uint32_t dst_base;          // index of the first destination pointer in BufTable
     uint32_t dst_copies;        // replicas of each row on the destination side
 };
@@ -118,6 +119,15 @@ __device__ __forceinline__ TileView locate_tile(const KParams &k, uint32_t tile)
         v.src_off = s.src_off + off;
         v.dst_off = s.dst_off + off;
         v.nbytes = left < k.tile_bytes ? (uint32_t)left : k.tile_bytes;
+    } else if (k.parts_per_row) {
+        // a piece of one row: dense on both sides, handled like a dense tile
+        const uint32_t row = t / k.parts_per_row;
+        const uint32_t off = (t - row * k.parts_per_row) * k.tile_bytes;
+        const uint32_t left = k.row_bytes - off;
+        v.pitch_rows = 1;
+        v.src_off = s.src_off + (uint64_t)row * k.row_bytes + off;
+        v.dst_off = s.dst_off + (uint64_t)row * s.pitch_rows * k.row_bytes + off;
+        v.nbytes = left < k.tile_bytes ? left : k.tile_bytes;
     } else {
         const uint64_t row0 = (uint64_t)t * k.rows_per_tile;
         const uint64_t rows_left = s.n_rows - row0;
@@ -550,6 +560,7 @@ int enqueue(const hp_plan *p, Direction dir, const hp::Launch &L, const BufTable
     k.tile_bytes = hp::tile_bytes_of(L.tile_variant);
     k.row_bytes = (uint32_t)p->row_bytes;
     k.rows_per_tile = std::max<uint32_t>(1u, k.tile_bytes / k.row_bytes);
+    k.parts_per_row = k.row_bytes >= k.tile_bytes ? (k.row_bytes + k.tile_bytes - 1) / k.tile_bytes : 0u;
     k.dst_base = (uint32_t)p->n_src_bufs;
     k.dst_copies = (uint32_t)p->dst_copies;
     LaunchCfg c;

@@ -132,11 +132,14 @@ int validate(const hp_layout_t *src, const hp_layout_t *dst, const hp_token_map_
     return HP_OK;
 }
 
-// Tiles of `tile` bytes needed by a segment: dense segments are cut by bytes,
-// row-strided ones by whole rows.  The kernels use the same two formulas.
+// Tiles of `tile` bytes needed by a segment: dense segments are cut by bytes.
+// Row-strided ones are cut row by row: a row at least one tile long is cut into
+// ceil(row / tile) dense pieces, shorter rows are grouped tile / row to a tile.
+// The kernels use the same formulas.
 uint64_t tiles_of(const hp_segment_t &s, int64_t row_bytes, uint32_t tile) {
     if (s.dst_row_stride == 1) return ((uint64_t)s.n_rows * row_bytes + tile - 1) / tile;
-    const uint64_t rows_per = std::max<uint64_t>(1, tile / (uint64_t)row_bytes);
+    if ((uint64_t)row_bytes >= tile) return (uint64_t)s.n_rows * (((uint64_t)row_bytes + tile - 1) / tile);
+    const uint64_t rows_per = tile / (uint64_t)row_bytes;
     return ((uint64_t)s.n_rows + rows_per - 1) / rows_per;
 }
 

@@ -650,3 +650,20 @@ def test_joined_plan_one_launch_for_all_edges(seed):
     for j in range(n_dst * n_maps):
         assert np.array_equal(_to_host_bits(g_dst[j]), o_dst[j]), j
     plan.close()
+
+
+@pytest.mark.parametrize("hidden,tile", [(600, 1024), (600, 4096), (2048, 1024), (1536, 2048), (520, 1024), (4096, 8192)])
+def test_sbh_rows_at_least_a_tile_long(hidden, tile):
+    """[S, B, H] destination order with two samples per rank: rows are strided on
+    the destination side.  Rows of at least a tile are cut into dense pieces
+    (including a short last piece), shorter ones are grouped."""
+    from parity import check_case_extended
+    rng = np.random.default_rng(hidden + tile)
+    tm = wl.token_map_from_lens(rng, 4, 96, hidden, [[5, 17, 9], [30], [], [12, 40]])
+    src = wl.Grid(tp=2, dp=3)
+    dst = wl.Grid(tp=2, cp=2, dp=2, cp_split=wl.CP_ZIGZAG, row_order=wl.ROW_SBH)
+    hp.hp_set_option("tile_bytes_fwd", tile)
+    hp.hp_set_option("tile_bytes_bwd", tile)
+    check_case(src, dst, tm, seed=hidden)
+    check_case_extended(src, dst, tm, seed=hidden)
+    check_case_extended(src, dst, replace(tm, dtype=wl.DT_F32), seed=hidden + 1)

@@ -223,11 +223,14 @@ def test_launch_shape_get_set_and_tile_counts():
     for bad in (dict(tile_bytes=3000), dict(block_threads=96), dict(waves_per_cu=40), dict(nontemporal=4)):
         with pytest.raises(hp.HpError):
             p.set_launch(0, **bad)
-    # row-strided segments are cut by whole rows
+    # row-strided segments: rows shorter than a tile are grouped, longer rows are cut into pieces
     tm = wl.TokenMap(2, 8, 600, [0, 1], [0, 2], [8, 5])
     q = hp.hp_plan_create_host(wl.Grid(), wl.Grid(row_order=wl.ROW_SBH), tm)
+    assert all(s.dst_row_stride == 2 for s in q.segments())
     q.set_launch(0, tile_bytes=4096)                      # 3 rows of 1200 B per tile
     assert q.info.n_tiles == sum(-(-s.n_rows // 3) for s in q.segments())
+    q.set_launch(0, tile_bytes=1024)                      # every row = 2 pieces (1024 + 176 B)
+    assert q.info.n_tiles == sum(2 * s.n_rows for s in q.segments())
     L = binding._lib()
     assert L.hp_plan_tune(None, None, None, None, None, None) == binding.HP_EINVAL
 
