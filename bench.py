@@ -272,43 +272,73 @@ def main() -> int:
 
     # ---- the CPU oracle on the same workload, host cores of this machine ----
     cpu_baseline = None
-    if not args.no_cpu_baseline and (args.accumulate or args.dtype != "bf16"):
-        log("[bench] cpu_baseline is only timed for the bf16 overwriting backward; skipped")
-    elif not args.no_cpu_baseline:
+    if not args.no_cpu_baseline:
         from oracle import oracle
         import numpy as np
         log("[bench] timing the CPU oracle on the same workload (first microbatch) ...")
         s, m = sets[0], maps[0]
         prob = oracle.Problem(w.src, w.dst, m)
-        bits = lambda t: t.cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+        if args.dtype == "f32":
+            host = lambda t: t.cpu().contiguous().numpy()
+            same = lambda a, b: np.array_equal(a.view(np.uint32), b.view(np.uint32))
+            ndt = np.float32
+        else:
+            host = lambda t: t.cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+            same = np.array_equal
+            ndt = np.uint16
         n_s, n_d = w.src.n_ranks, w.dst.n_ranks            # microbatch 0 = the first buffers of the set
-        h_src = [bits(t) for t in s["src"][:n_s]]
-        h_dst = [bits(t) for t in s["dst"][:n_d]]
-        h_grad = [bits(t) for t in s["grad"][:n_d]]
-        h_sg = [np.zeros((r, H), np.uint16) for r in prob.src_rows()]
+        if args.accumulate:
+            # the accumulators have been added to an unknown number of times: start them from zero
+            # and run one more hp_backward_accumulate, the call the oracle is compared with
+            for t in s["sgrad"]:
+                t.zero_()
+            torch.cuda.synchronize()
+            s["plan"].backward_accumulate_raw(s["pgd"], s["pgs"], stream)
+            stream.synchronize()
+        h_src = [host(t) for t in s["src"][:n_s]]
+        h_dst = [host(t) for t in s["dst"][:n_d]]
+        h_grad = [host(t) for t in s["grad"][:n_d]]
         ncores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count()
         ncores = min(ncores, int(os.environ.get("OMP_NUM_THREADS", ncores)))
         res = {}
         for nt in (ncores, 1):
+            h_sg = [np.zeros((r, H), np.float32 if args.accumulate else ndt) for r in prob.src_rows()]
             oracle.set_threads(nt)
             t0 = time.perf_counter()
             prob.forward(h_src, h_dst)
             t1 = time.perf_counter()
-            prob.backward_bf16(h_grad, h_sg)
+            if args.accumulate:
+                prob.backward_accumulate(h_grad, h_sg)
+            elif args.dtype == "f32":
+                prob.backward_f32(h_grad, h_sg)
+            else:
+                prob.backward_bf16(h_grad, h_sg)
             t2 = time.perf_counter()
             res[nt] = (t1 - t0, t2 - t1)
             log(f"[bench] oracle {nt} thread(s): fwd {t1 - t0:.3f} s, bwd {t2 - t1:.3f} s")
         p0 = s["plan"].info
-        ob = (1 + 2 * p0.dst_copies + p0.src_copies) * m.n_rows * H * 2
+        ob = (1 + p0.dst_copies) * m.n_rows * p0.row_bytes + (
+            p0.dst_copies * m.n_rows * p0.row_bytes + p0.src_copies * 2 * m.n_rows * H * 4 if args.accumulate
+            else (p0.dst_copies + p0.src_copies) * m.n_rows * p0.row_bytes)
         cpu_baseline = {
             "value": ob / sum(res[ncores]) / 1e9, "unit": "GB/s", "cores": ncores, "kind": "oracle",
             "sample": f"one full forward+backward pass of {w.name} (microbatch 0), {ob / 1e9:.2f} GB algorithmic",
             "fwd_s": res[ncores][0], "bwd_s": res[ncores][1],
             "one_thread_value": ob / sum(res[1]) / 1e9, "one_thread_fwd_s": res[1][0], "one_thread_bwd_s": res[1][1],
         }
-        # the GPU result of the last step must equal what the oracle just computed
-        ok = all(np.array_equal(bits(t), h) for t, h in zip(s["sgrad"][:n_s], h_sg))
-        cpu_baseline["gpu_matches_oracle"] = bool(ok)
+        # The GPU results of the last step must equal what the oracle just computed: the source
+        # gradients everywhere, the destination buffers on every image-token row (the oracle's
+        # forward has just rewritten those rows of the GPU's own output; text rows are whatever
+        # the random prefill was).
+        if args.accumulate:                                    # binary32 accumulators whatever the gradients' dtype
+            ok_b = all(np.array_equal(t.cpu().numpy().view(np.uint32), h.view(np.uint32))
+                       for t, h in zip(s["sgrad"][:n_s], h_sg))
+        else:
+            ok_b = all(same(host(t), h) for t, h in zip(s["sgrad"][:n_s], h_sg))
+        ok_f = all(same(host(t), h) for t, h in zip(s["dst"][:n_d], h_dst))
+        cpu_baseline["gpu_matches_oracle"] = bool(ok_b and ok_f)
+        cpu_baseline["gpu_matches_oracle_forward"] = bool(ok_f)
+        cpu_baseline["gpu_matches_oracle_backward"] = bool(ok_b)
 
     out = {
         "metric": "boundary fwd+bwd effective HBM GB/s and % of MI355X HBM peak, 1 GPU",

@@ -95,13 +95,16 @@ def check_case(src_grid, dst_grid, tm, seed=1, gen_device="cpu", stream=None, ch
     return info
 
 
-def check_case_extended(src_grid, dst_grid, tm, seed=1):
+def check_case_extended(src_grid, dst_grid, tm, seed=1, acc_launch=None):
     """binary32 payloads (forward, backward) and the accumulating backward for
-    the token map's dtype, bit for bit against the oracle."""
+    the token map's dtype, bit for bit against the oracle.  acc_launch: launch
+    shape for hp_backward_accumulate instead of the default."""
     dev = "cuda:0"
     is_f32 = tm.dtype == wl.DT_F32
     tdt, ndt = (torch.float32, np.float32) if is_f32 else (torch.bfloat16, np.uint16)
     plan = hp.hp_plan_create(src_grid, dst_grid, tm)
+    if acc_launch is not None:
+        plan.set_launch(2, **acc_launch)
     prob = oracle.Problem(src_grid, dst_grid, tm)
     H, rows, drows = tm.hidden, prob.src_rows(), prob.dst_rows()
 

@@ -408,6 +408,20 @@ def test_f32_and_accumulate_long_context_spans(hidden, dtype):
     check_case_extended(w.src, w.dst, replace(w.maps[0], hidden=hidden, dtype=dtype), seed=hidden)
 
 
+@pytest.mark.parametrize("tile,block,waves,nt", [(1024, 64, 16, 3), (2048, 64, 14, 3), (1024, 128, 0, 0),
+                                                 (8192, 256, 8, 1), (65536, 1024, 32, 2), (2048, 256, 4, 3)])
+def test_accumulate_launch_shapes(tile, block, waves, nt):
+    """hp_backward_accumulate in launch shapes its tuner may pick (small tiles
+    included), bf16 and binary32 gradients, ragged tile ends."""
+    from parity import check_case_extended
+    w = wl.scaled(wl.long_context(n_images=9), 264)
+    shape = dict(tile_bytes=tile, block_threads=block, waves_per_cu=waves, nontemporal=nt)
+    check_case_extended(w.src, w.dst, w.maps[0], seed=tile % 89, acc_launch=shape)
+    check_case_extended(w.src, w.dst, replace(w.maps[0], dtype=wl.DT_F32), seed=tile % 83, acc_launch=shape)
+    w5 = wl.scaled(wl.large_scale(), 72)                         # TP_dst 8, two source copies
+    check_case_extended(w5.src, w5.dst, w5.maps[0], seed=block, acc_launch=shape)
+
+
 def test_accumulate_large_scale_replicas():
     """TP_dst = 8, TP_src = 2 (both source copies accumulate), hidden 96."""
     from parity import check_case_extended
