@@ -166,8 +166,10 @@ typedef struct hp_segment {
  * destination coordinate and batch interval" step (Colocated communicator,
  * second paragraph; both sides build the same static routing pattern,
  * Non-colocated communicator): validates the two grids and the token map,
- * builds the per-segment and per-tile gather/scatter tables on the host and
- * uploads them to the CURRENT HIP device (one synchronous allocation + copy).
+ * builds the segment table (runs of rows contiguous on both sides) and the
+ * search trees that map a workgroup to its segment on the host, and uploads
+ * them to the CURRENT HIP device (a few KB; one synchronous copy into a device
+ * block that is recycled from earlier plans when one is free).
  * src, dst, map: host structs, read only during the call.
  * *out receives an owned plan; release it with hp_plan_destroy. */
 int hp_plan_create(const hp_layout_t *src, const hp_layout_t *dst,
@@ -242,7 +244,7 @@ int hp_plan_segments(const hp_plan_t *plan, hp_segment_t *out, int32_t cap);
  * fan-in concatenation in batch order, Non-colocated communicator; insertion
  * into the text embeddings, "Pipeline schedule details" phase 2).
  *   src_bufs: HOST array of n_src_bufs DEVICE pointers, index tp + TP_src*dp,
- *             each [rows_i, hidden] bf16.  Only copies with tp == 0 are read;
+ *             each [rows_i, hidden] of the plan's dtype.  Only copies with tp == 0 are read;
  *             entries of other copies and of empty ranks may be NULL.
  *   dst_bufs: HOST array of n_dst_bufs DEVICE pointers, index
  *             tp + TP_dst*(cp + CP_dst*dp), each [dst_rows_per_buf, hidden].
@@ -260,7 +262,7 @@ int hp_forward(const hp_plan_t *plan, const void *const *src_bufs,
  * backward splits along the recorded intervals; the result is placed on every
  * TP rank of the source side, Non-colocated communicator, backward paragraph).
  * The dst_copies replicas of each image-token row are summed in binary32 in
- * ascending tp order and rounded once to bf16.
+ * ascending tp order and rounded once to bf16 (HP_F32: no final rounding).
  *   dst_grad_bufs: HOST array of n_dst_bufs DEVICE pointers, same shapes as
  *                  hp_forward's dst_bufs; only image-token rows are read.
  *   src_grad_bufs: HOST array of n_src_bufs DEVICE pointers; every row of
@@ -317,7 +319,7 @@ int hp_plan_set_launch(hp_plan_t *plan, int32_t direction, const hp_launch_t *in
  * concurrently with other calls that use the same plan.
  * The winning shapes are also remembered per problem class (dtype, row size,
  * TP_dst copies, TP_src copies, device): plans of the same class created later
- * by hp_plan_create / hp_plan_create_batched start from them instead of the
+ * by hp_plan_create / hp_plan_create_batched / hp_plan_create_joined start from them instead of the
  * process-wide defaults, so a caller that rebuilds its plan every step tunes
  * once.  hp_forget_tuned_shapes drops what was remembered. */
 int hp_plan_tune(hp_plan_t *plan, const void *const *src_bufs, void *const *dst_bufs,
@@ -359,8 +361,11 @@ int hp_probe_stream(int32_t n_read, int32_t n_write, int64_t bytes_per_array,
  * kernel dispatch until the n pairs are used up; later launches are not timed.
  * n = 0 disables timing and frees the events.  hp_profile_read waits for the
  * recorded launches, writes their kernel durations in milliseconds to ms[] and
- * their kind (0 = hp_forward, 1 = hp_backward, 2 = hp_backward_accumulate) to kinds[] (host arrays of `cap`
- * entries), rewinds the recorder and returns the number of launches recorded. */
+ * their kind (0 = hp_forward, 1 = hp_backward, 2 = hp_backward_accumulate) to
+ * kinds[] (host arrays of `cap` entries), rewinds the recorder and returns the
+ * number of launches recorded.  A launch that carries events goes through the
+ * extended launch call and cannot be recorded into a HIP graph; with timing
+ * disabled every launch is a plain kernel launch and can. */
 int hp_profile_enable(int32_t max_launches);
 int hp_profile_read(float *ms, int32_t *kinds, int32_t cap);
 
