@@ -56,8 +56,9 @@ def main() -> int:
                     help="record one step into a HIP graph and time its replays (wall clock); kernel "
                          "durations still come from eager launches carrying events")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-tune", action="store_true",
-                    help="keep the default launch shapes instead of calling hp_plan_tune before the timed region")
+    ap.add_argument("--tune", action="store_true",
+                    help="call hp_plan_tune (measured launch-shape search, ~0.5 s) before the warm-up instead of "
+                         "keeping the launch shapes a new plan starts from")
     ap.add_argument("--dtype", default="bf16", choices=["bf16", "f32"], help="payload element type")
     ap.add_argument("--seq-shard", action="store_true",
                     help="destination TP ranks hold sequence shards instead of replicas (sequence parallelism)")
@@ -133,7 +134,7 @@ def main() -> int:
 
     # ---- one-time launch-shape search on the resident buffers (not part of a step) ----
     tune_ms = None
-    if not args.no_tune:
+    if args.tune:
         t0 = time.perf_counter()
         s = sets[0]                      # plans of one workload share their grids: tune one, copy its shapes
         if args.accumulate:              # tune on scratch accumulators: every candidate launch adds into them
@@ -350,7 +351,7 @@ def main() -> int:
                    "batch": maps[0].batch, "seq": maps[0].seq, "hidden": H, "microbatches": len(maps),
                    "tp_mode": "seq_shard" if args.seq_shard else "replicate", "row_order": args.row_order,
                    "backward": "accumulate_f32" if args.accumulate else "overwrite",
-                   "accumulate_dtype": "f32", "launches_per_direction": n_launch, "launch_shapes": shapes, "tuned": not args.no_tune,
+                   "accumulate_dtype": "f32", "launches_per_direction": n_launch, "launch_shapes": shapes, "tuned": args.tune,
                    "submission": "hip_graph_replay" if args.graph else "eager",
                    "image_rows": int(sum(m.n_rows for m in maps)), "boundary_bytes": boundary,
                    },

@@ -290,7 +290,8 @@ int hp_backward_accumulate(const hp_plan_t *plan, const void *const *dst_grad_bu
 /* Launch shape of one direction of a plan (direction 0 = hp_forward,
  * 1 = hp_backward, 2 = hp_backward_accumulate).  A plan starts from the
  * process-wide defaults below (the accumulating backward from the backward
- * defaults with tiles of at least 4 KiB). */
+ * defaults, with tiles of at least 4 KiB when a tile size is set there), or
+ * from what hp_plan_tune found earlier for the same problem class. */
 typedef struct hp_launch {
     int32_t tile_bytes;      /* boundary bytes per workgroup: 1024 << k, k = 0..6              */
     int32_t block_threads;   /* workgroup size: multiple of 64 in [64, 1024]                   */
@@ -314,6 +315,10 @@ int hp_plan_set_launch(hp_plan_t *plan, int32_t direction, const hp_launch_t *in
  * direction is followed by a launch of the other direction with its current
  * shape, and the pair is what is timed: a shape is judged in the sequence
  * forward, backward, forward, ... rather than against copies of itself.
+ * A plan whose hp_forward launch moves less than 1 GiB keeps its shapes (it
+ * still gets one launch per given direction): a timing loop over so little data
+ * runs out of the 256 MB memory-side cache and would rank shapes by a behaviour
+ * that a training step's fresh buffers do not show.
  * SYNCHRONOUS: waits on `stream` repeatedly, takes tens to hundreds of
  * milliseconds, creates and destroys four HIP events, and must not run
  * concurrently with other calls that use the same plan.
@@ -337,7 +342,13 @@ int hp_plan_tune_accumulate(hp_plan_t *plan, const void *const *dst_grad_bufs,
  * Keys: "tile_bytes_fwd", "tile_bytes_bwd", "block_threads_fwd",
  * "block_threads_bwd", "waves_per_cu_fwd", "waves_per_cu_bwd",
  * "nontemporal_fwd", "nontemporal_bwd"; meanings and ranges as in hp_launch_t.
+ * The tile size and the resident-wave cap also take HP_AUTO (-1, their initial
+ * value): the plan then picks them from its replica counts - the more buffers a
+ * row's traffic spreads over (1 + TP_dst forward, TP_dst + TP_src backward) the
+ * lower the cap, so that about 100 KB per compute unit stay in flight; the
+ * figures are what hp_plan_tune finds most often per replica count.
  * Returns HP_EINVAL for an unknown key or an out-of-range value. */
+#define HP_AUTO (-1)
 int hp_set_option(const char *key, int64_t value);
 int64_t hp_get_option(const char *key);     /* INT64_MIN for an unknown key */
 

@@ -832,14 +832,14 @@ struct OptionDesc {
     bool tile;
 };
 const OptionDesc kOptions[] = {
-    {"tile_bytes_fwd", &hp::Options::tile_bytes_fwd, 1024, 65536, 1, true},
-    {"tile_bytes_bwd", &hp::Options::tile_bytes_bwd, 1024, 65536, 1, true},
+    {"tile_bytes_fwd", &hp::Options::tile_bytes_fwd, -1, 65536, 1, true},
+    {"tile_bytes_bwd", &hp::Options::tile_bytes_bwd, -1, 65536, 1, true},
     {"block_threads_fwd", &hp::Options::block_threads_fwd, 64, 1024, 64, false},
     {"block_threads_bwd", &hp::Options::block_threads_bwd, 64, 1024, 64, false},
     {"nontemporal_fwd", &hp::Options::nontemporal_fwd, 0, 3, 1, false},
     {"nontemporal_bwd", &hp::Options::nontemporal_bwd, 0, 3, 1, false},
-    {"waves_per_cu_fwd", &hp::Options::waves_per_cu_fwd, 0, 32, 1, false},
-    {"waves_per_cu_bwd", &hp::Options::waves_per_cu_bwd, 0, 32, 1, false},
+    {"waves_per_cu_fwd", &hp::Options::waves_per_cu_fwd, -1, 32, 1, false},
+    {"waves_per_cu_bwd", &hp::Options::waves_per_cu_bwd, -1, 32, 1, false},
 };
 
 // Four events for timing a burst: the first dispatch carries (e[0], e[1]), the
@@ -856,6 +856,9 @@ struct BurstEvents {
             if (x) (void)hipEventDestroy(x);
     }
 };
+
+// hp_plan_tune searches only plans whose forward launch moves at least this much.
+constexpr int64_t kMinTunedBytes = (int64_t)1 << 30;
 
 // What runs right after every candidate launch while it is being timed: the
 // plan's other direction with its current launch shape, when the caller gave
@@ -1133,6 +1136,17 @@ int hp_plan_tune(hp_plan_t *p, const void *const *src_bufs, void *const *dst_buf
     if (rc == HP_OK && dst_grad_bufs)
         rc = prepare(p, kBackward, (const void *const *)src_grad_bufs, dst_grad_bufs, &bt_b, &lane_b);
     const bool both = src_bufs && dst_grad_bufs;
+    // A timing loop over a small plan runs out of the 256 MB memory-side cache and
+    // ranks shapes by a behaviour that a training step's fresh buffers do not
+    // show: such plans keep their shapes and get one plain launch per direction.
+    const int64_t boundary = p->n_rows * p->row_bytes;
+    if (rc == HP_OK && (1 + (int64_t)p->dst_copies) * boundary < kMinTunedBytes) {
+        if (src_bufs) rc = enqueue(p, kForward, p->fwd, bt_f, lane_f, (hipStream_t)stream, EventPair{});
+        if (rc == HP_OK && dst_grad_bufs)
+            rc = enqueue(p, kBackward, p->bwd, bt_b, lane_b, (hipStream_t)stream, EventPair{});
+        if (rc == HP_OK && hip_failed(hipStreamSynchronize((hipStream_t)stream))) rc = HP_EHIP;
+        return rc;
+    }
     if (rc == HP_OK && src_bufs) {
         const Companion co{kBackward, p->bwd, &bt_b, lane_b};
         rc = tune_direction(p, kForward, bt_f, lane_f, (hipStream_t)stream, both ? &co : nullptr);
@@ -1224,6 +1238,11 @@ int hp_plan_tune_accumulate(hp_plan_t *p, const void *const *dst_grad_bufs, void
     BufTable bt;
     int lane = 0;
     int rc = prepare(p, kBackwardAcc, (const void *const *)src_accum_bufs, dst_grad_bufs, &bt, &lane);
+    if (rc == HP_OK && p->bwd_accum_bytes < kMinTunedBytes) {              // as in hp_plan_tune: no search
+        rc = enqueue(p, kBackwardAcc, p->acc, bt, lane, (hipStream_t)stream, EventPair{});
+        if (rc == HP_OK && hip_failed(hipStreamSynchronize((hipStream_t)stream))) rc = HP_EHIP;
+        return rc;
+    }
     if (rc == HP_OK) rc = tune_direction(p, kBackwardAcc, bt, lane, (hipStream_t)stream, nullptr);
     if (rc == HP_OK) g_shapes.remember(p, false, false, true);
     return rc;
@@ -1234,7 +1253,7 @@ int hp_set_option(const char *key, int64_t value) {
     for (const OptionDesc &d : kOptions) {
         if (std::strcmp(key, d.name)) continue;
         if (value < d.lo || value > d.hi || (d.multiple > 1 && value % d.multiple)) return HP_EINVAL;
-        if (d.tile && hp::tile_variant_of(value) < 0) return HP_EINVAL;
+        if (d.tile && value != HP_AUTO && hp::tile_variant_of(value) < 0) return HP_EINVAL;
         hp::options().*(d.field) = value;
         return HP_OK;
     }

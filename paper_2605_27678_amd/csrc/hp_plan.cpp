@@ -193,6 +193,36 @@ int make_tables(hp_plan *p) {
     return HP_OK;
 }
 
+// Launch shapes for a new plan.  Both kernels are fastest when roughly 100 KB
+// of traffic per compute unit is in flight, so the resident-wave cap that suits
+// a plan falls as the number of buffers a row's traffic spreads over rises:
+// 1 + dst_copies for forward, dst_copies + src_copies for backward.  The table
+// is what the measured search (hp_plan_tune) picks most often per replica count
+// on the five workloads and their sequence-sharded variants; an option that is
+// not HP_AUTO overrides its field.
+void default_launches(hp_plan *p) {
+    const Options &o = options();
+    const int c = p->dst_copies, s = p->src_copies;
+    Launch f{1, 64, c <= 1 ? 24 : c == 2 ? 14 : c <= 4 ? 12 : c <= 7 ? 8 : 5, 2};          // 2 KiB tiles
+    Launch b = c + s <= 2 ? Launch{1, 64, 30, 3} : c + s == 3 ? Launch{0, 64, 30, 3} : Launch{0, 64, 16, 3};
+    // accumulating backward: the binary32 accumulators are read and written, 2 * 4 / elem_bytes row sizes per copy
+    const int acc_streams = c + s * 8 / p->elem_bytes;
+    Launch a{1, 64, std::min(24, std::max(4, (100 + acc_streams / 2) / acc_streams)), 3};
+    auto apply = [](Launch &L, int64_t tile, int64_t block, int64_t waves, int64_t nt) {
+        if (tile > 0) L.tile_variant = tile_variant_of(tile);
+        L.block = (int32_t)block;
+        if (waves >= 0) L.waves_per_cu = (int32_t)waves;
+        L.nontemporal = (int32_t)nt;
+    };
+    apply(f, o.tile_bytes_fwd, o.block_threads_fwd, o.waves_per_cu_fwd, o.nontemporal_fwd);
+    apply(b, o.tile_bytes_bwd, o.block_threads_bwd, o.waves_per_cu_bwd, o.nontemporal_bwd);
+    apply(a, o.tile_bytes_bwd > 0 ? std::max<int64_t>(o.tile_bytes_bwd, 4096) : -1, o.block_threads_bwd,
+          o.waves_per_cu_bwd, o.nontemporal_bwd);
+    p->fwd = f;
+    p->bwd = b;
+    p->acc = a;
+}
+
 // No two spans of one microbatch may overlap, whichever edge they belong to.
 int check_cross_edge_overlap(const hp_token_map_t *maps, int32_t n_edges, int32_t n_maps) {
     struct Span { int32_t b; int64_t s, e; };
@@ -333,13 +363,7 @@ int build_host_plan(const hp_layout_t *srcs, int32_t n_edges, const hp_layout_t 
     }
     p->n_src_bufs = edge_base;
 
-    const Options &o = options();
-    p->fwd = Launch{tile_variant_of(o.tile_bytes_fwd), (int32_t)o.block_threads_fwd,
-                    (int32_t)o.waves_per_cu_fwd, (int32_t)o.nontemporal_fwd};
-    p->bwd = Launch{tile_variant_of(o.tile_bytes_bwd), (int32_t)o.block_threads_bwd,
-                    (int32_t)o.waves_per_cu_bwd, (int32_t)o.nontemporal_bwd};
-    p->acc = p->bwd;
-    p->acc.tile_variant = std::max(p->acc.tile_variant, 2);   // the read-modify-write side prefers >= 4 KiB tiles
+    default_launches(p);
     return make_tables(p);
 }
 

@@ -339,16 +339,17 @@ def test_batched_plan_full_non_colocated():
 
 
 def test_tune_keeps_results_exact_and_picks_a_valid_shape():
-    w = wl.scaled(wl.long_context(), 1024)
+    H = 2816                                   # forward moves 1.13 GB: above the size the tuner searches from
+    w = wl.scaled(wl.long_context(), H)
     tm = w.maps[0]
     plan = hp.hp_plan_create(w.src, w.dst, tm)
     prob = oracle.Problem(w.src, w.dst, tm)
     rows, drows = plan.src_rows(), plan.info.dst_rows_per_buf
-    src = [wl.random_bf16((r, 1024), 5 + i, "cuda") for i, r in enumerate(rows)]
-    dst = [wl.random_bf16((drows, 1024), 50 + j, "cuda") for j in range(32)]
-    grad = [wl.random_bf16((drows, 1024), 90 + j, "cuda") for j in range(32)]
+    src = [wl.random_bf16((r, H), 5 + i, "cuda") for i, r in enumerate(rows)]
+    dst = [wl.random_bf16((drows, H), 50 + j, "cuda") for j in range(32)]
+    grad = [wl.random_bf16((drows, H), 90 + j, "cuda") for j in range(32)]
     pre = [_to_host_bits(t).copy() for t in dst]
-    sg = [torch.zeros((r, 1024), dtype=torch.bfloat16, device="cuda") for r in rows]
+    sg = [torch.zeros((r, H), dtype=torch.bfloat16, device="cuda") for r in rows]
     st = torch.cuda.Stream()
     torch.cuda.synchronize()
     hp.hp_plan_tune(plan, src, dst, grad, sg, st)
@@ -358,7 +359,7 @@ def test_tune_keeps_results_exact_and_picks_a_valid_shape():
         assert 0 <= L["waves_per_cu"] <= 32
     # the buffers hold what one forward / backward would have produced
     prob.forward([_to_host_bits(t) for t in src], pre)
-    o_sg = [np.zeros((r, 1024), np.uint16) for r in rows]
+    o_sg = [np.zeros((r, H), np.uint16) for r in rows]
     prob.backward_bf16([_to_host_bits(t) for t in grad], o_sg)
     for j in range(32):
         assert np.array_equal(_to_host_bits(dst[j]), pre[j])
@@ -372,12 +373,65 @@ def test_tune_keeps_results_exact_and_picks_a_valid_shape():
     hp.hp_plan_tune(plan, src, dst, None, None, st)          # one direction only
     # a later plan of the same problem class starts from the tuned shapes
     tuned = (plan.get_launch(0), plan.get_launch(1))
-    other = hp.hp_plan_create(w.src, w.dst, wl.scaled(wl.long_context(n_images=5), 1024).maps[0])
+    other = hp.hp_plan_create(w.src, w.dst, wl.scaled(wl.long_context(n_images=5), H).maps[0])
     assert (other.get_launch(0), other.get_launch(1)) == tuned
     hp.hp_forget_tuned_shapes()
     fresh = hp.hp_plan_create(w.src, w.dst, tm)
-    assert fresh.get_launch(0)["tile_bytes"] == hp.hp_get_option("tile_bytes_fwd")
-    assert fresh.get_launch(0)["waves_per_cu"] == hp.hp_get_option("waves_per_cu_fwd")
+    untuned = hp.hp_plan_create_host(w.src, w.dst, tm)
+    assert [fresh.get_launch(d) for d in (0, 1, 2)] == [untuned.get_launch(d) for d in (0, 1, 2)]
+    assert fresh.get_launch(0) == dict(tile_bytes=2048, block_threads=64, waves_per_cu=12, nontemporal=2)
+
+
+def test_tune_accumulate_picks_a_valid_shape_and_keeps_the_sum_exact():
+    H = 2048                                   # 1.3 GB per accumulating launch: searched
+    w = wl.scaled(wl.long_context(), H)
+    tm = w.maps[0]
+    plan = hp.hp_plan_create(w.src, w.dst, tm)
+    prob = oracle.Problem(w.src, w.dst, tm)
+    rows, drows = plan.src_rows(), plan.info.dst_rows_per_buf
+    grad = [wl.random_bf16((drows, H), 190 + j, "cuda") for j in range(32)]
+    scratch = [torch.zeros((r, H), dtype=torch.float32, device="cuda") for r in rows]
+    plan.tune_accumulate(grad, scratch, torch.cuda.current_stream())
+    L = plan.get_launch(2)
+    assert L["tile_bytes"] in (1024, 2048, 4096, 8192) and L["block_threads"] in (64, 128, 256)
+    other = hp.hp_plan_create(w.src, w.dst, wl.scaled(wl.long_context(n_images=4), H).maps[0])
+    assert other.get_launch(2) == L                     # remembered for the problem class
+    acc = [torch.zeros_like(t) for t in scratch]
+    hp.hp_backward_accumulate(plan, grad, acc)
+    torch.cuda.synchronize()
+    want = [np.zeros((r, H), np.float32) for r in rows]
+    prob.backward_accumulate([_to_host_bits(t) for t in grad], want)
+    for a, b in zip(acc, want):
+        assert np.array_equal(a.cpu().numpy().view(np.uint32), b.view(np.uint32))
+    # a small plan keeps its shape
+    small = hp.hp_plan_create(w.src, w.dst, wl.scaled(wl.long_context(n_images=4), 64).maps[0])
+    before = small.get_launch(2)
+    g2 = [wl.random_bf16((drows, 64), 7 + j, "cuda") for j in range(32)]
+    small.tune_accumulate(g2, [torch.zeros((r, 64), dtype=torch.float32, device="cuda") for r in small.src_rows()])
+    assert small.get_launch(2) == before
+
+
+def test_tune_leaves_small_plans_alone():
+    """Less than 1 GiB per forward launch: no search (it would be timed out of
+    the memory-side cache); the buffers still end up as after one call."""
+    w = wl.scaled(wl.long_context(n_images=6), 256)
+    tm = w.maps[0]
+    plan = hp.hp_plan_create(w.src, w.dst, tm)
+    before = [plan.get_launch(d) for d in (0, 1, 2)]
+    prob = oracle.Problem(w.src, w.dst, tm)
+    src, pre, grads = make_inputs(prob, 12, "cuda")
+    dst = [t.clone() for t in pre]
+    sg = [torch.zeros_like(t) for t in src]
+    hp.hp_plan_tune(plan, src, dst, grads, sg, torch.cuda.current_stream())
+    assert [plan.get_launch(d) for d in (0, 1, 2)] == before
+    want = [_to_host_bits(t).copy() for t in pre]
+    prob.forward([_to_host_bits(t) for t in src], want)
+    o_sg = [np.zeros((r, 256), np.uint16) for r in prob.src_rows()]
+    prob.backward_bf16([_to_host_bits(t) for t in grads], o_sg)
+    assert all(np.array_equal(_to_host_bits(a), b) for a, b in zip(dst, want))
+    assert all(np.array_equal(_to_host_bits(a), b) for a, b in zip(sg, o_sg))
+    other = hp.hp_plan_create(w.src, w.dst, tm)          # nothing was remembered for this problem class
+    assert [other.get_launch(d) for d in (0, 1, 2)] == before
 
 
 def test_stream_probe_reports_a_rate():

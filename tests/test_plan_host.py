@@ -107,7 +107,7 @@ def test_full_size_infos():
     w = wl.long_context()
     p = hp.hp_plan_create_host(w.src, w.dst, w.maps[0])
     assert p.info.row_bytes == 10240 and p.info.dst_rows_per_buf == 16384
-    assert p.info.n_tiles >= p.info.boundary_bytes // hp.hp_get_option("tile_bytes_fwd")
+    assert p.info.n_tiles >= p.info.boundary_bytes // p.get_launch(0)["tile_bytes"]
     w = wl.large_scale()
     p = hp.hp_plan_create_host(w.src, w.dst, w.maps[0])
     assert (p.info.n_src_bufs, p.info.n_dst_bufs, p.info.src_copies, p.info.dst_copies) == (32, 32, 2, 8)
@@ -318,3 +318,41 @@ def test_joined_plan_errors():
     with pytest.raises(hp.HpError) as ei:
         hp.hp_plan_create_joined([wl.Grid(dp=223), wl.Grid(dp=222)], dst, [[a], [empty]], host_only=True)
     assert ei.value.code == binding.HP_ELAYOUT
+
+
+def test_default_launch_shapes_follow_the_replica_counts():
+    """HP_AUTO: the resident-wave cap falls as a row's traffic spreads over more
+    buffers; explicit options override field by field."""
+    tm = wl.TokenMap(1, 64, 64, [0], [8], [16])
+    caps_f, caps_b = [], []
+    for tp in (1, 2, 4, 8, 16):
+        p = hp.hp_plan_create_host(wl.Grid(), wl.Grid(tp=tp), tm)
+        f, b, a = p.get_launch(0), p.get_launch(1), p.get_launch(2)
+        assert f["tile_bytes"] == 2048 and f["block_threads"] == 64 and f["nontemporal"] == 2
+        assert b["tile_bytes"] in (1024, 2048) and b["nontemporal"] == 3
+        assert 4 <= a["waves_per_cu"] <= 24 and a["tile_bytes"] == 2048
+        caps_f.append(f["waves_per_cu"])
+        caps_b.append(b["waves_per_cu"] * b["tile_bytes"])
+    assert caps_f == sorted(caps_f, reverse=True) and caps_f[0] > caps_f[-1]
+    assert caps_b == sorted(caps_b, reverse=True)
+    lc = hp.hp_plan_create_host(wl.Grid(dp=8), wl.Grid(tp=4, cp=8, cp_split=wl.CP_ZIGZAG),
+                                wl.TokenMap(1, 64, 64, [0], [8], [16]))
+    assert lc.get_launch(0) == dict(tile_bytes=2048, block_threads=64, waves_per_cu=12, nontemporal=2)
+    assert lc.get_launch(1) == dict(tile_bytes=1024, block_threads=64, waves_per_cu=16, nontemporal=3)
+    saved = {k: hp.hp_get_option(k) for k in ("tile_bytes_fwd", "waves_per_cu_bwd", "tile_bytes_bwd")}
+    assert set(saved.values()) == {-1}
+    try:
+        hp.hp_set_option("tile_bytes_fwd", 8192)
+        hp.hp_set_option("waves_per_cu_bwd", 0)
+        hp.hp_set_option("tile_bytes_bwd", 1024)
+        q = hp.hp_plan_create_host(wl.Grid(), wl.Grid(tp=8), tm)
+        assert q.get_launch(0)["tile_bytes"] == 8192 and q.get_launch(0)["waves_per_cu"] == 5   # cap still automatic
+        assert q.get_launch(1)["waves_per_cu"] == 0 and q.get_launch(1)["tile_bytes"] == 1024
+        assert q.get_launch(2)["tile_bytes"] == 4096 and q.get_launch(2)["waves_per_cu"] == 0
+        with pytest.raises(hp.HpError):
+            hp.hp_set_option("tile_bytes_fwd", 3000)
+        with pytest.raises(hp.HpError):
+            hp.hp_set_option("waves_per_cu_fwd", -2)
+    finally:
+        for k, v in saved.items():
+            hp.hp_set_option(k, v)
