@@ -281,6 +281,41 @@ def random_layout_case(rng: np.random.Generator, max_seq_units: int = 6):
     return src, dst, tm
 
 
+def random_wide_case(rng: np.random.Generator):
+    """A medium-size random problem with wide grids (CP up to 16, destination TP
+    up to 16, many images of very different lengths, up to 8 samples): more
+    segments than one search-tree node holds, spans across many chunk borders."""
+    while True:
+        tp_s = int(rng.choice([1, 2, 4]))
+        dp_s = int(rng.choice([1, 3, 8, 16, 32]))
+        tp_d = int(rng.choice([1, 2, 5, 8, 16]))
+        cp_d = int(rng.choice([1, 2, 4, 8, 16]))
+        dp_d = int(rng.choice([1, 2, 4]))
+        if tp_s * dp_s + tp_d * cp_d * dp_d <= 448:          # the library's buffer limit
+            break
+    batch = dp_d * int(rng.choice([1, 2]))
+    seq = 2 * cp_d * tp_d * int(rng.integers(2, 40))
+    hidden = int(rng.choice([8, 12, 64]))
+    lens_per_sample = []
+    for _ in range(batch):
+        lens, budget = [], int(seq * rng.uniform(0.2, 1.0))
+        while budget > 0 and len(lens) < 40:
+            ln = min(budget, int(rng.choice([1, 2, 7, 33, 150, 700])))
+            lens.append(ln)
+            budget -= ln
+        lens_per_sample.append(lens)
+    tm = token_map_from_lens(rng, batch, seq, hidden, lens_per_sample)
+    if rng.random() < 0.3:
+        tm = shuffle_spans(rng, tm)
+    if tm.n_images and rng.random() < 0.5:
+        tm.img_src_dp = np.sort(rng.integers(0, dp_s, size=tm.n_images)).astype(np.int32)
+    src = Grid(tp=tp_s, dp=dp_s)
+    dst = Grid(tp=tp_d, cp=cp_d, dp=dp_d, cp_split=int(rng.choice([CP_CONTIGUOUS, CP_ZIGZAG])),
+               row_order=int(rng.choice([ROW_BSH, ROW_SBH])),
+               tp_mode=int(rng.choice([TP_REPLICATE, TP_SEQ_SHARD])))
+    return src, dst, tm
+
+
 def random_bf16(shape, seed: int, device: str = "cpu", scale: float = 1.0):
     """N(0, scale^2) drawn in fp32 by torch's seeded generator on `device`, then
     rounded to bf16 by torch.  Returns a torch.bfloat16 tensor on `device`."""

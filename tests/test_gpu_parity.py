@@ -53,6 +53,23 @@ def test_spans_out_of_position_order(seed):
     check_case(src, dst, wl.shuffle_spans(rng, tm), seed=seed)
 
 
+@pytest.mark.parametrize("seed", list(range(14)) + [50])          # seed 50: 404 segments, three tree levels
+def test_random_wide_grids(seed):
+    """CP up to 16, destination TP up to 16 (run-time replica counts 5 and 16),
+    hundreds of segments: search trees of two and three levels; 1 KiB tiles so
+    that most segments span several tiles with ragged ends."""
+    from parity import check_case_extended
+    rng = np.random.default_rng(4100 + seed)
+    src, dst, tm = wl.random_wide_case(rng)
+    hp.hp_set_option("tile_bytes_fwd", 1024)
+    hp.hp_set_option("tile_bytes_bwd", 1024)
+    check_case(src, dst, tm, seed=seed)
+    if seed % 2:
+        check_case_extended(src, dst, replace(tm, dtype=wl.DT_F32), seed=seed)
+    else:
+        check_case_extended(src, dst, tm, seed=seed)
+
+
 @pytest.mark.parametrize("k", [1, 2, 7, 8, 9, 32])
 def test_long_context_image_counts(k):
     """Config-3 grid with 1..32 images: empty source ranks when k < 8."""

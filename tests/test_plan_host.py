@@ -79,6 +79,21 @@ def test_segments_match_oracle_walk_spans_out_of_position_order(seed):
     check_against_oracle(src, dst, wl.shuffle_spans(rng, tm))
 
 
+@pytest.mark.parametrize("seed", range(30))
+def test_segments_match_oracle_walk_wide_grids(seed):
+    """CP up to 16, TP up to 16, hundreds of segments (search trees of two and
+    three levels), sequence-sharded or replicated."""
+    rng = np.random.default_rng(4000 + seed)
+    src, dst, tm = wl.random_wide_case(rng)
+    plan = hp.hp_plan_create_host(src, dst, tm)
+    prob = oracle.Problem(src, dst, tm)
+    assert plan.src_rows() == prob.src_rows() and plan.info.n_rows == tm.n_rows
+    sb, sr = expand_segments(plan)
+    for j in range(prob.n_dst):
+        osb, osr = prob.forward_map(j)
+        assert np.array_equal(sb[j], osb) and np.array_equal(sr[j], osr), j
+
+
 @pytest.mark.parametrize("k", [1, 2, 7, 8, 9, 32])
 def test_segments_match_oracle_walk_long_context_image_counts(k):
     """Fewer images than source ranks (empty ranks), exactly as many, one more,
