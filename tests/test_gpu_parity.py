@@ -752,3 +752,13 @@ def test_sbh_rows_at_least_a_tile_long(hidden, tile):
     check_case(src, dst, tm, seed=hidden)
     check_case_extended(src, dst, tm, seed=hidden)
     check_case_extended(src, dst, replace(tm, dtype=wl.DT_F32), seed=hidden + 1)
+
+
+@pytest.mark.parametrize("row_order", [wl.ROW_BSH, wl.ROW_SBH])
+def test_very_long_rows(row_order):
+    """2 MiB rows (hidden 2^20): every tile lies inside one row; with [S,B,H]
+    order and two samples per rank the rows are cut into dense pieces."""
+    H = 1 << 20
+    tm = wl.TokenMap(2, 8, H, [0, 1, 1], [1, 0, 5], [3, 2, 3])
+    check_case(wl.Grid(tp=2, dp=2), wl.Grid(tp=2, cp=2, cp_split=wl.CP_ZIGZAG, row_order=row_order), tm, seed=9,
+               gen_device="cuda")

@@ -371,3 +371,20 @@ def test_default_launch_shapes_follow_the_replica_counts():
     finally:
         for k, v in saved.items():
             hp.hp_set_option(k, v)
+
+
+def test_size_limits():
+    """Rows up to 16 MiB; at most 2^31 - 1 tiles of 1 KiB per launch (a 2 TiB boundary)."""
+    g = wl.Grid()
+    one_row = lambda hidden: wl.TokenMap(1, 4, hidden, [0], [1], [2])
+    p = hp.hp_plan_create_host(g, wl.Grid(tp=2), one_row(1 << 23))           # 16 MiB rows
+    assert p.info.row_bytes == 1 << 24 and p.info.n_tiles == 2 * (1 << 24) // p.get_launch(0)["tile_bytes"]
+    assert _code(g, g, one_row((1 << 23) + 8)) == binding.HP_ELAYOUT
+    assert _code(g, g, replace(one_row((1 << 22) + 4), dtype=wl.DT_F32)) == binding.HP_ELAYOUT
+    big = wl.TokenMap(1, 1 << 20, 1 << 20, [0], [0], [1 << 20])              # 2 TiB boundary: one tile too many
+    assert _code(g, g, big) == binding.HP_ELAYOUT
+    ok = wl.TokenMap(1, 1 << 20, 1 << 20, [0], [0], [(1 << 20) - 1])
+    q = hp.hp_plan_create_host(g, wl.Grid(cp=2, cp_split=wl.CP_ZIGZAG), ok)
+    assert q.info.boundary_bytes == ((1 << 20) - 1) << 21 and q.info.n_segments == 3   # chunks 1 and 2 sit back to back on rank 1
+    q.set_launch(0, tile_bytes=1024)
+    assert q.info.n_tiles == q.info.boundary_bytes // 1024
