@@ -260,7 +260,10 @@ def main() -> int:
     dominant = "hp_backward_kernel" if b_avg >= f_avg else "hp_forward_kernel"
     dom_bytes = (bwd_bytes if dominant == "hp_backward_kernel" else fwd_bytes) / n_launch
     dom_ms = (b_avg if dominant == "hp_backward_kernel" else f_avg) / n_launch
-    traffic = read_traffic(w.name)
+    # the committed counter summary describes the workload's plain configuration only
+    plain = args.dtype == "bf16" and not (args.accumulate or args.seq_shard or args.per_microbatch) \
+        and args.row_order == "bsh"
+    traffic = read_traffic(w.name) if plain else {}
     tkey = "backward_bytes_per_launch" if dominant == "hp_backward_kernel" else "forward_bytes_per_launch"
     roofline = {
         "bound": "hbm", "kernel": dominant,
