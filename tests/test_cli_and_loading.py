@@ -45,3 +45,17 @@ def test_product_package_does_not_import_the_oracle():
                     code = line.split("#")[0].split("//")[0]
                     if "import" in code or "include" in code or "CDLL" in code or "open(" in code:
                         assert "oracle" not in code.lower(), (os.path.join(dirpath, f), line)
+
+
+@pytest.mark.parametrize("compiler,std", [("gcc", "-std=c99"), ("g++", "-std=c++11")])
+def test_header_is_plain_c(compiler, std, tmp_path):
+    """include/hp.h compiles on its own as strict C99 and as C++: no HIP or
+    torch types cross the boundary."""
+    src = tmp_path / ("t.c" if compiler == "gcc" else "t.cpp")
+    src.write_text('#include "hp.h"\nint main(void) { hp_launch_t l; hp_plan_info_t i; (void)l; (void)i; '
+                   'return sizeof(hp_layout_t) == 32 && HP_AUTO == -1 ? 0 : 1; }\n')
+    exe = tmp_path / "t"
+    r = subprocess.run([compiler, std, "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                        str(src), "-o", str(exe)], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stderr
+    assert subprocess.run([str(exe)], timeout=30).returncode == 0
