@@ -388,3 +388,28 @@ def test_size_limits():
     assert q.info.boundary_bytes == ((1 << 20) - 1) << 21 and q.info.n_segments == 3   # chunks 1 and 2 sit back to back on rank 1
     q.set_launch(0, tile_bytes=1024)
     assert q.info.n_tiles == q.info.boundary_bytes // 1024
+
+
+def test_plan_builder_fuzz_under_sanitizers(tmp_path):
+    """The host plan builder (pure C++) compiled with ASan + UBSan and driven with
+    40000 random inputs, valid and invalid: no sanitizer report, every segment
+    of every accepted plan inside its buffers."""
+    import subprocess
+    exe = tmp_path / "fuzz_plan"
+    csrc = os.path.join(ROOT, "paper_2605_27678_amd", "csrc")
+
+    def build(sanitizers):
+        r = subprocess.run(["g++", "-std=c++17", "-O1", "-g", *sanitizers, "-fno-sanitize-recover=all",
+                            "-I", os.path.join(ROOT, "include"), "-I", csrc, os.path.join(ROOT, "tests", "fuzz_plan.cpp"),
+                            os.path.join(csrc, "hp_plan.cpp"), "-o", str(exe)], capture_output=True, text=True, timeout=300)
+        assert r.returncode == 0, r.stderr
+
+    build(["-fsanitize=address,undefined", "-static-libasan"])
+    first = subprocess.run([str(exe), "11", "10"], capture_output=True, text=True, timeout=300)
+    if first.returncode != 0 and "ASan runtime does not come first" in first.stderr:
+        build(["-fsanitize=undefined"])              # another library is preloaded here: UBSan only
+    for seed in (11, 12):
+        r = subprocess.run([str(exe), str(seed), "20000"], capture_output=True, text=True, timeout=300)
+        assert r.returncode == 0, r.stdout + r.stderr
+        accepted = int(r.stdout.split()[1])
+        assert accepted > 2000, r.stdout
