@@ -22,8 +22,13 @@
 
 #include "hp.h"
 #include "hp_plan.hpp"
+#include "hp_tile.hpp"
 
 namespace {
+
+using hp::KParams;
+using hp::TileView;
+using hp::locate_tile;
 
 thread_local int g_last_hip_error = 0;
 
@@ -40,20 +45,6 @@ struct BufTable {
     void *p[HP_MAX_BUFFERS];
 };
 
-// Everything else a kernel needs, also by value.
-struct KParams {
-    const hp::Seg *segs;        // segment descriptors
-    const uint32_t *tree;       // search trees (64-byte aligned nodes of 16 keys)
-    uint32_t n_levels;          // levels of this launch's tree
-    uint32_t level_off[hp::kMaxTreeLevels];   // start of each level, in keys; level 0 = leaves
-    uint32_t tile_bytes;
-    uint32_t row_bytes;
-    uint32_t rows_per_tile;     // row-strided segments, rows shorter than a tile: tile_bytes / row_bytes
-    uint32_t parts_per_row;     // row-strided segments, rows of at least a tile: ceil(row_bytes / tile_bytes); else 0
-    uint32_t dst_base;          // index of the first destination pointer in BufTable
-    uint32_t dst_copies;        // replicas of each row on the destination side
-};
-
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
@@ -67,78 +58,6 @@ __device__ __forceinline__ void st(V *p, V v) {
     if constexpr (NT) __builtin_nontemporal_store(v, p);
     else *p = v;
 }
-
-// One workgroup's share of the launch.
-struct TileView {
-    uint64_t src_off, dst_off;  // bytes from the buffer bases
-    uint32_t nbytes;
-    uint32_t pitch_rows;        // 1 = dense destination
-    uint32_t src_buf, dst_buf0;
-    uint32_t src_copies;        // identical TP copies of the source rank
-};
-
-// One node of the search tree: 16 ascending keys (padding = UINT32_MAX) fetched
-// with one 64-byte scalar load.  Returns how many keys are <= tile, and the
-// largest of them.
-__device__ __forceinline__ void search_node(const uint32_t *node, uint32_t tile, uint32_t &count, uint32_t &key) {
-    const uint32_t *p = (const uint32_t *)__builtin_assume_aligned(node, 64);
-    uint32_t c = 0, best = 0;
-#pragma unroll
-    for (int j = 0; j < hp::kTreeFanout; ++j) {
-        const uint32_t v = p[j];
-        const bool le = v <= tile;
-        c += le ? 1u : 0u;
-        best = le ? v : best;
-    }
-    count = c;
-    key = best;
-}
-
-// Scalar code: every value here is uniform over the workgroup.  One dependent
-// scalar load per tree level, then the descriptor, then the buffer pointers.
-__device__ __forceinline__ TileView locate_tile(const KParams &k, uint32_t tile) {
-    uint32_t lo = 0, first = 0;
-#pragma unroll
-    for (int l = hp::kMaxTreeLevels - 1; l >= 0; --l) {
-        if ((uint32_t)l < k.n_levels) {
-            uint32_t count;
-            search_node(k.tree + k.level_off[l] + (size_t)lo * hp::kTreeFanout, tile, count, first);
-            lo = lo * hp::kTreeFanout + count - 1;
-        }
-    }
-    const hp::Seg s = k.segs[lo];
-    const uint32_t t = tile - first;
-    TileView v;
-    v.pitch_rows = s.pitch_rows;
-    v.src_buf = s.src_buf;
-    v.dst_buf0 = s.dst_buf0;
-    v.src_copies = s.src_copies;
-    if (s.pitch_rows == 1) {
-        const uint64_t off = (uint64_t)t * k.tile_bytes;
-        const uint64_t left = (uint64_t)s.n_rows * k.row_bytes - off;
-        v.src_off = s.src_off + off;
-        v.dst_off = s.dst_off + off;
-        v.nbytes = left < k.tile_bytes ? (uint32_t)left : k.tile_bytes;
-    } else if (k.parts_per_row) {
-        // a piece of one row: dense on both sides, handled like a dense tile
-        const uint32_t row = t / k.parts_per_row;
-        const uint32_t off = (t - row * k.parts_per_row) * k.tile_bytes;
-        const uint32_t left = k.row_bytes - off;
-        v.pitch_rows = 1;
-        v.src_off = s.src_off + (uint64_t)row * k.row_bytes + off;
-        v.dst_off = s.dst_off + (uint64_t)row * s.pitch_rows * k.row_bytes + off;
-        v.nbytes = left < k.tile_bytes ? left : k.tile_bytes;
-    } else {
-        const uint64_t row0 = (uint64_t)t * k.rows_per_tile;
-        const uint64_t rows_left = s.n_rows - row0;
-        const uint32_t rows = rows_left < k.rows_per_tile ? (uint32_t)rows_left : k.rows_per_tile;
-        v.src_off = s.src_off + row0 * k.row_bytes;
-        v.dst_off = s.dst_off + row0 * s.pitch_rows * k.row_bytes;
-        v.nbytes = rows * k.row_bytes;
-    }
-    return v;
-}
-
 
 // ---------------------------------------------------------------------------
 // forward: tile of the source buffer -> the same bytes in NREP destination copies
@@ -552,17 +471,7 @@ enum Direction { kForward = 0, kBackward = 1, kBackwardAcc = 2 };
 // lane chunk chosen by prepare(): bytes for forward, elements for backward.
 int enqueue(const hp_plan *p, Direction dir, const hp::Launch &L, const BufTable &bt, int lane,
             hipStream_t stream, EventPair ev) {
-    KParams k;
-    k.segs = p->d_segs;
-    k.tree = p->d_tree;
-    k.n_levels = p->tree_info[L.tile_variant].n_levels;
-    for (int l = 0; l < hp::kMaxTreeLevels; ++l) k.level_off[l] = p->tree_info[L.tile_variant].level_off[l];
-    k.tile_bytes = hp::tile_bytes_of(L.tile_variant);
-    k.row_bytes = (uint32_t)p->row_bytes;
-    k.rows_per_tile = std::max<uint32_t>(1u, k.tile_bytes / k.row_bytes);
-    k.parts_per_row = k.row_bytes >= k.tile_bytes ? (k.row_bytes + k.tile_bytes - 1) / k.tile_bytes : 0u;
-    k.dst_base = (uint32_t)p->n_src_bufs;
-    k.dst_copies = (uint32_t)p->dst_copies;
+    const KParams k = hp::kernel_params(*p, L.tile_variant, p->d_segs, p->d_tree);
     LaunchCfg c;
     c.grid = dim3(p->n_tiles(L.tile_variant));
     c.block = dim3((unsigned)L.block);
