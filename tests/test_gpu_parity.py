@@ -687,7 +687,9 @@ def test_joined_plan_one_launch_for_all_edges(seed):
     rng = np.random.default_rng(900 + seed)
     n_edges, n_maps = 2 + seed % 2, 2
     B, S, H = 2, 512, (64, 40, 7)[seed % 3]
-    dst = wl.Grid(tp=(2, 3, 4)[seed % 3], cp=2, dp=1 + seed % 2, cp_split=wl.CP_ZIGZAG if seed % 2 else wl.CP_CONTIGUOUS)
+    dst = wl.Grid(tp=(2, 3, 4)[seed % 3], cp=2, dp=1 + seed % 2, cp_split=wl.CP_ZIGZAG if seed % 2 else wl.CP_CONTIGUOUS,
+                  tp_mode=wl.TP_SEQ_SHARD if seed in (3, 5) else wl.TP_REPLICATE,
+                  row_order=wl.ROW_SBH if seed == 2 else wl.ROW_BSH)
     srcs = [wl.Grid(tp=1 + (e + seed) % 2, dp=int(rng.choice([1, 2, 3, 4])), rank_offset=16 * e) for e in range(n_edges)]
     maps = [[None] * n_maps for _ in range(n_edges)]
     for m in range(n_maps):
