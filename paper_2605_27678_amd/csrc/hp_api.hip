@@ -14,6 +14,7 @@
 #include <hip/hip_ext.h>
 
 #include <algorithm>
+#include <atomic>
 #include <cstdint>
 #include <cstring>
 #include <mutex>
@@ -359,7 +360,7 @@ struct Profiler {
     std::vector<hipEvent_t> start, stop;
     std::vector<int32_t> kind;
     size_t used = 0;
-    bool enabled = false;
+    std::atomic<bool> enabled{false};
 } g_prof;
 
 struct EventPair { hipEvent_t start = nullptr, stop = nullptr; };
@@ -1163,6 +1164,7 @@ int hp_set_option(const char *key, int64_t value) {
         if (std::strcmp(key, d.name)) continue;
         if (value < d.lo || value > d.hi || (d.multiple > 1 && value % d.multiple)) return HP_EINVAL;
         if (d.tile && value != HP_AUTO && hp::tile_variant_of(value) < 0) return HP_EINVAL;
+        std::lock_guard<std::mutex> lk(hp::options_mutex());
         hp::options().*(d.field) = value;
         return HP_OK;
     }
@@ -1172,7 +1174,10 @@ int hp_set_option(const char *key, int64_t value) {
 int64_t hp_get_option(const char *key) {
     if (key)
         for (const OptionDesc &d : kOptions)
-            if (!std::strcmp(key, d.name)) return hp::options().*(d.field);
+            if (!std::strcmp(key, d.name)) {
+                std::lock_guard<std::mutex> lk(hp::options_mutex());
+                return hp::options().*(d.field);
+            }
     return INT64_MIN;
 }
 

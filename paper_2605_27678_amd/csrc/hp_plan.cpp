@@ -23,6 +23,11 @@ Options &options() {
     return o;
 }
 
+std::mutex &options_mutex() {
+    static std::mutex m;
+    return m;
+}
+
 int tile_variant_of(int64_t tile_bytes) {
     for (int v = 0; v < kTileVariants; ++v)
         if (tile_bytes == (int64_t)tile_bytes_of(v)) return v;
@@ -201,7 +206,11 @@ int make_tables(hp_plan *p) {
 // on the five workloads and their sequence-sharded variants; an option that is
 // not HP_AUTO overrides its field.
 void default_launches(hp_plan *p) {
-    const Options &o = options();
+    Options o;
+    {
+        std::lock_guard<std::mutex> lk(options_mutex());
+        o = options();
+    }
     const int c = p->dst_copies, s = p->src_copies;
     Launch f{1, 64, c <= 1 ? 24 : c == 2 ? 14 : c <= 4 ? 12 : c <= 7 ? 8 : 5, 2};          // 2 KiB tiles
     Launch b = c + s <= 2 ? Launch{1, 64, 30, 3} : c + s == 3 ? Launch{0, 64, 30, 3} : Launch{0, 64, 16, 3};

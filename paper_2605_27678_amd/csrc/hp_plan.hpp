@@ -58,7 +58,8 @@ struct Options {
     int64_t waves_per_cu_fwd = -1, waves_per_cu_bwd = -1;   // 0 = no cap
     int64_t nontemporal_fwd = 2, nontemporal_bwd = 3;       // bit 0 loads, bit 1 stores
 };
-Options &options();
+Options &options();             // guarded by options_mutex()
+std::mutex &options_mutex();
 int tile_variant_of(int64_t tile_bytes);   // -1 unless 1 KiB << v, v < kTileVariants
 
 }  // namespace hp

@@ -764,3 +764,44 @@ def test_very_long_rows(row_order):
     tm = wl.TokenMap(2, 8, H, [0, 1, 1], [1, 0, 5], [3, 2, 3])
     check_case(wl.Grid(tp=2, dp=2), wl.Grid(tp=2, cp=2, cp_split=wl.CP_ZIGZAG, row_order=row_order), tm, seed=9,
                gen_device="cuda")
+
+
+def test_one_plan_from_several_threads_and_streams():
+    """A plan is immutable after creation: four host threads, each with its own
+    stream and buffers, run forward and backward on the same plan at once."""
+    import threading
+    w = wl.scaled(wl.long_context(n_images=12), 512)
+    tm = w.maps[0]
+    plan = hp.hp_plan_create(w.src, w.dst, tm)
+    prob = oracle.Problem(w.src, w.dst, tm)
+    sets, errors = [], []
+    for k in range(4):
+        src, pre, grads = make_inputs(prob, 50 + k, "cuda")
+        sets.append(dict(src=src, pre=pre, dst=[t.clone() for t in pre], grads=grads,
+                         sg=[torch.zeros_like(t) for t in src], stream=torch.cuda.Stream()))
+    torch.cuda.synchronize()
+
+    def work(s):
+        try:
+            for _ in range(5):
+                hp.hp_forward(plan, s["src"], s["dst"], s["stream"])
+                hp.hp_backward(plan, s["grads"], s["sg"], s["stream"])
+            s["stream"].synchronize()
+        except Exception as e:                      # noqa: BLE001 - reported below
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=work, args=(s,)) for s in sets]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    assert not errors, errors
+    for s in sets:
+        want = [_to_host_bits(t).copy() for t in s["pre"]]
+        prob.forward([_to_host_bits(t) for t in s["src"]], want)
+        assert all(np.array_equal(_to_host_bits(a), b) for a, b in zip(s["dst"], want))
+        o_sg = [np.zeros((r, 512), np.uint16) for r in prob.src_rows()]
+        prob.backward_bf16([_to_host_bits(t) for t in s["grads"]], o_sg)
+        assert all(np.array_equal(_to_host_bits(a), b) for a, b in zip(s["sg"], o_sg))
+    plan.close()                                    # records one event on each of the four streams
+    hp.hp_plan_create(w.src, w.dst, tm).close()

@@ -438,3 +438,31 @@ def test_every_tile_of_every_launch_shape_stays_in_bounds(tmp_path):
     r = subprocess.run([str(exe), "21", "300"], capture_output=True, text=True, timeout=600)
     assert r.returncode == 0, r.stdout + r.stderr
     assert int(r.stdout.split()[3]) > 1000000, r.stdout
+
+
+def test_plans_from_several_threads():
+    """Host-only plan creation, queries and option changes from eight threads at
+    once (the binding releases the GIL inside the library)."""
+    import threading
+    errors = []
+
+    def work(seed):
+        try:
+            rng = np.random.default_rng(seed)
+            for i in range(60):
+                src, dst, tm = wl.random_layout_case(rng)
+                p = hp.hp_plan_create_host(src, dst, tm)
+                assert p.info.n_rows == tm.n_rows
+                assert p.get_launch(0)["tile_bytes"] in (1024, 2048, 4096)
+                hp.hp_set_option("tile_bytes_fwd", (1024, 2048, 4096, -1)[i % 4])
+                p.close()
+        except Exception as e:                      # noqa: BLE001 - reported below
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=work, args=(s,)) for s in range(8)]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join()
+    hp.hp_set_option("tile_bytes_fwd", -1)
+    assert not errors, errors
