@@ -805,3 +805,27 @@ def test_one_plan_from_several_threads_and_streams():
         assert all(np.array_equal(_to_host_bits(a), b) for a, b in zip(s["sg"], o_sg))
     plan.close()                                    # records one event on each of the four streams
     hp.hp_plan_create(w.src, w.dst, tm).close()
+
+
+def test_readme_example_runs_as_written():
+    """The calls of the README's usage section, with its grids and token map."""
+    from paper_2605_27678_amd import Grid, TokenMap
+    src = Grid(tp=1, dp=8)
+    dst = Grid(tp=4, cp=8, dp=1, cp_split=1)
+    tm = TokenMap(batch=1, seq=131072, hidden=5120,
+                  img_sample=[0, 0], img_start=[100, 9000], img_len=[576, 2304])
+    plan = hp.hp_plan_create(src, dst, tm)
+    rows, drows = plan.src_rows(), plan.info.dst_rows_per_buf
+    assert sum(rows) == 2880 and drows == 16384 and plan.info.n_dst_bufs == 32
+    src_bufs = [wl.random_bf16((r, 5120), 3 + i, "cuda") for i, r in enumerate(rows)]
+    dst_bufs = [torch.zeros((drows, 5120), dtype=torch.bfloat16, device="cuda") for _ in range(32)]
+    dst_grads = [torch.ones((drows, 5120), dtype=torch.bfloat16, device="cuda") for _ in range(32)]
+    src_grads = [torch.empty_like(t) for t in src_bufs]
+    stream = torch.cuda.current_stream()
+    hp.hp_plan_tune(plan, src_bufs, dst_bufs, dst_grads, src_grads)
+    hp.hp_forward(plan, src_bufs, dst_bufs, stream)
+    hp.hp_backward(plan, dst_grads, src_grads, stream)
+    torch.cuda.synchronize()
+    assert all(bool((g == 4).all()) for g in src_grads if g.numel())          # all-ones gradients return TP_dst
+    written = sum(int((d != 0).any(dim=1).sum()) for d in dst_bufs)
+    assert written == 4 * 2880                                                # image rows only, in all four replicas
