@@ -270,6 +270,8 @@ def main() -> int:
         "achieved": dom_bytes / dom_ms / 1e6, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
         "frac": dom_bytes / dom_ms / 1e6 / HBM_PEAK_GBPS,
         "traffic": traffic.get(tkey),
+        "bytes_moved_per_boundary_byte": traffic.get(tkey.replace("_bytes_per_launch", "_bytes_per_boundary_byte")),
+        "algorithmic_bytes_per_boundary_byte": dom_bytes * n_launch / boundary if boundary else None,
         "algorithmic_bytes_per_launch": dom_bytes,
         "avg_launch_ms": dom_ms,
     }
