@@ -1242,6 +1242,6 @@ const char *hp_strerror(int code) {
 
 int hp_last_hip_error(void) { return g_last_hip_error; }
 
-const char *hp_version(void) { return "hp-boundary 0.2 (gfx950)"; }
+const char *hp_version(void) { return "hp-boundary 0.3 (gfx950)"; }
 
 }  // extern "C"
