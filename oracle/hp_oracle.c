@@ -94,6 +94,14 @@ static uint16_t f32_to_bf16(float f)
 }
 
 uint16_t orc_f32_to_bf16(float f) { return f32_to_bf16(f); }
+/* Same, from the bit pattern: a signalling NaN does not survive being passed
+ * through a host language's double, so tests hand the bits over as an integer. */
+uint16_t orc_f32_bits_to_bf16(uint32_t bits)
+{
+    float f;
+    memcpy(&f, &bits, 4);
+    return f32_to_bf16(f);
+}
 float orc_bf16_to_f32(uint16_t h) { return bf16_to_f32(h); }
 
 /* ---- source side -------------------------------------------------------- */

@@ -52,6 +52,8 @@ def lib():
         _lib.orc_dst_rows.restype = C.c_int64
         _lib.orc_f32_to_bf16.restype = C.c_uint16
         _lib.orc_f32_to_bf16.argtypes = [C.c_float]
+        _lib.orc_f32_bits_to_bf16.restype = C.c_uint16
+        _lib.orc_f32_bits_to_bf16.argtypes = [C.c_uint32]
         _lib.orc_bf16_to_f32.restype = C.c_float
         _lib.orc_bf16_to_f32.argtypes = [C.c_uint16]
     return _lib
@@ -172,6 +174,12 @@ class Problem:
 
 def f32_to_bf16(x: float) -> int:
     return int(lib().orc_f32_to_bf16(C.c_float(x)))
+
+
+def f32_bits_to_bf16(bits: int) -> int:
+    """Rounds the binary32 value with this bit pattern (keeps signalling NaNs
+    as they are on the way in)."""
+    return int(lib().orc_f32_bits_to_bf16(C.c_uint32(bits)))
 
 
 def bf16_to_f32(h: int) -> float:

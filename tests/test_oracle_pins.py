@@ -474,6 +474,7 @@ def test_fixed_order_fold_and_rounding_fixture():
     for case in g["round"]:
         f = struct.unpack("<f", struct.pack("<I", int(case["f32_hex"], 16)))[0]
         assert oracle.f32_to_bf16(f) == int(case["bf16_hex"], 16), case["why"]
+        assert oracle.f32_bits_to_bf16(int(case["f32_hex"], 16)) == int(case["bf16_hex"], 16), case["why"]
     for case in g["fold"]:
         terms = case["terms"]
         tp = len(terms)
@@ -492,8 +493,10 @@ def test_bf16_rounding_matches_torch_cast():
     f = bits.view(np.float32)
     t = torch.from_numpy(f.copy()).to(torch.bfloat16)
     want = wl.bf16_bits(t)
-    for x, w in zip(f.tolist()[:4000], want.tolist()[:4000]):
-        got = oracle.f32_to_bf16(x)
+    for x, u, w in zip(f.tolist()[:4000], bits.tolist()[:4000], want.tolist()[:4000]):
+        got = oracle.f32_bits_to_bf16(u)
+        if x == x:
+            assert got == oracle.f32_to_bf16(x)
         if x != x:
             assert (got & 0x7F80) == 0x7F80 and (got & 0x7F) != 0      # NaN stays NaN
         else:
@@ -638,3 +641,164 @@ def test_accumulate_adds_the_fold_to_what_is_there():
     acc = [np.array([[16777216.0]], np.float32)]
     prob.backward_accumulate([_f2b([[1.0]]), _f2b([[1.0]])], acc)     # fold = 2; 2^24 + 2 is exact
     assert float(acc[0][0, 0]) == 16777218.0
+
+
+# ----------------------------------------------------------------------------
+# backward by "un-slicing": every destination-gradient buffer is put back into a
+# global [B, S, H] gradient (one per TP copy), the copies are folded with numpy
+# float32 adds, the result is rounded with torch's bf16 cast, and the image rows
+# are read out in global image order and cut into the source buffers.  Nothing
+# of the oracle is used; both destination TP modes.
+# ----------------------------------------------------------------------------
+
+def brute_backward(src, dst, tm, grads_f32):
+    """grads_f32: one float32 [rows, H] array per destination buffer.  Returns
+    the folded binary32 gradient of every source buffer (before any rounding)."""
+    B, S, H = tm.batch, tm.seq, tm.hidden
+    ids = np.arange(B * S, dtype=np.int64).reshape(B, S)
+    where = brute_slice(dst, tm, ids)                     # global position of every local row
+    n_copies = 1 if dst.tp_mode == wl.TP_SEQ_SHARD else dst.tp
+    G = np.zeros((n_copies, B * S, H), np.float32)
+    seen = np.zeros((n_copies, B * S), np.int32)
+    for j, pos in enumerate(where):
+        t = j % dst.tp if n_copies > 1 else 0
+        G[t, pos] = grads_f32[j]
+        seen[t, pos] += 1
+    assert np.all(seen == 1)                              # every copy tiles the fused tensor exactly once
+    fold = G[0].copy()
+    for t in range(1, n_copies):                          # ascending tp, one IEEE binary32 add each
+        fold = (fold + G[t]).astype(np.float32)
+    img_pos = np.concatenate([int(b) * S + np.arange(int(s), int(s) + int(ln)) for b, s, ln in
+                              zip(tm.img_sample, tm.img_start, tm.img_len)]) if tm.n_images \
+        else np.zeros(0, np.int64)
+    return brute_sources(src, tm, fold[img_pos])
+
+
+def seq_shard_case(rng, tp=None):
+    """A random small layout whose destination is sequence-sharded over `tp`
+    ranks (drawn again until the CP-local sequence divides)."""
+    from dataclasses import replace
+    for _ in range(1000):
+        src, dst, tm = wl.random_layout_case(rng)
+        t = dst.tp if tp is None else tp
+        if (tm.seq // dst.cp) % t == 0 and tm.n_images:
+            return src, replace(dst, tp=t, tp_mode=wl.TP_SEQ_SHARD), tm
+    raise AssertionError("no case drawn")
+
+
+def wide_range_grads(rng, prob, hidden):
+    e = rng.integers(-12, 12, size=(prob.n_dst, prob.dst_rows(), hidden))
+    return [(rng.standard_normal((prob.dst_rows(), hidden)) * np.exp2(e[j])).astype(np.float32)
+            for j in range(prob.n_dst)]
+
+
+@pytest.mark.parametrize("mode", ["replicate", "seq_shard"])
+@pytest.mark.parametrize("seed", range(12))
+def test_backward_matches_global_unslicing(seed, mode):
+    rng = np.random.default_rng(8000 + seed)
+    if mode == "seq_shard":
+        src, dst, tm = seq_shard_case(rng, tp=(2, 3, 4)[seed % 3])
+    else:
+        src, dst, tm = wl.random_layout_case(rng)
+    prob = oracle.Problem(src, dst, tm)
+    gb = [_f2b(x) for x in wide_range_grads(rng, prob, tm.hidden)]           # bf16 bit patterns
+    want_f32 = brute_backward(src, dst, tm, [_b2f(x) for x in gb])
+    want_bits = [_f2b(x) for x in want_f32]                                  # torch's rounding
+    for call in (prob.backward_bf16, lambda g, out: prob._backward(0, False, g, out)):
+        sg = [np.full((r, tm.hidden), 0x7FC1, np.uint16) for r in prob.src_rows()]
+        call(gb, sg)
+        for a, w in zip(sg, want_bits):
+            assert np.array_equal(a, w), (seed, mode)
+    # binary32 gradients: no rounding at the end
+    gf = wide_range_grads(rng, prob, tm.hidden)
+    want = brute_backward(src, dst, tm, gf)
+    out = [np.full((r, tm.hidden), np.nan, np.float32) for r in prob.src_rows()]
+    prob.backward_f32(gf, out)
+    for a, w in zip(out, want):
+        assert np.array_equal(a.view(np.uint32), w.view(np.uint32)), (seed, mode)
+    # accumulating output: start + fold, one more binary32 add
+    start = [rng.standard_normal((r, tm.hidden)).astype(np.float32) for r in prob.src_rows()]
+    for g, w_fold in ((gb, want_f32), (gf, want)):
+        acc = [a.copy() for a in start]
+        prob.backward_accumulate(g, acc)
+        for a, s0, w in zip(acc, start, w_fold):
+            assert np.array_equal(a.view(np.uint32), (s0 + w).astype(np.float32).view(np.uint32)), (seed, mode)
+
+
+@pytest.mark.parametrize("tp", [2, 3, 4])
+def test_seq_sharded_backward_is_the_inverse_permutation_of_forward(tp):
+    """Sequence-sharded TP replicates nothing, so there is nothing to sum:
+    backward applied to forward's output returns the source bit for bit, and
+    all-ones gradients come back as 1 (not TP_dst)."""
+    rng = np.random.default_rng(8100 + tp)
+    for _ in range(6):
+        src, dst, tm = seq_shard_case(rng, tp=tp)
+        X = row_id_payload(tm.n_rows, tm.hidden) & np.uint16(0x3FFF)          # finite, all different
+        prob, srcs, dsts = run_oracle_forward(src, dst, tm, X, text_value=0x7FC0)
+        for call in (prob.backward_bf16, lambda g, out: prob._backward(0, False, g, out)):
+            sg = [np.full(a.shape, 0x7FC1, np.uint16) for a in srcs]
+            call(dsts, sg)
+            for a, b in zip(sg, srcs):
+                assert np.array_equal(a, b)
+        ones = [_f2b(np.ones((prob.dst_rows(), tm.hidden), np.float32)) for _ in range(prob.n_dst)]
+        sg = [np.full(a.shape, 0x7FC1, np.uint16) for a in srcs]
+        prob.backward_bf16(ones, sg)
+        for a in sg:
+            assert np.array_equal(_b2f(a), np.ones(a.shape, np.float32))
+        of = [np.ones((prob.dst_rows(), tm.hidden), np.float32) for _ in range(prob.n_dst)]
+        out = [np.full(a.shape, np.nan, np.float32) for a in srcs]
+        prob.backward_f32(of, out)
+        assert all(np.array_equal(a, np.ones_like(a)) for a in out)
+        acc = [np.full(a.shape, 5.0, np.float32) for a in srcs]
+        prob.backward_accumulate(of, acc)
+        assert all(np.array_equal(a, np.full_like(a, 6.0)) for a in acc)
+
+
+@pytest.mark.parametrize("seed", range(9))
+def test_seq_sharded_backward_adjoint_and_text_rows(seed):
+    rng = np.random.default_rng(8200 + seed)
+    src, dst, tm = seq_shard_case(rng, tp=(2, 3, 4)[seed % 3])
+    prob = oracle.Problem(src, dst, tm)
+    Xf = rng.integers(-8, 9, size=(tm.n_rows, tm.hidden)).astype(np.float32)
+    srcs = brute_sources(src, tm, _f2b(Xf))
+    dsts = [_f2b(np.zeros((prob.dst_rows(), tm.hidden), np.float32)) for _ in range(prob.n_dst)]
+    prob.forward(srcs, dsts)
+    gf = [rng.integers(-8, 9, size=(prob.dst_rows(), tm.hidden)).astype(np.float32) for _ in range(prob.n_dst)]
+    sg = [np.full((r, tm.hidden), 0x7FC1, np.uint16) for r in prob.src_rows()]
+    prob.backward_bf16([_f2b(x) for x in gf], sg)
+    lhs = 0.0
+    for j in range(prob.n_dst):
+        sb, _ = prob.forward_map(j)
+        lhs += float((_b2f(dsts[j]).astype(np.float64) * gf[j])[sb >= 0].sum())
+    rhs = sum(float((_b2f(srcs[i]).astype(np.float64) * _b2f(sg[i])).sum()) for i in range(0, prob.n_src, src.tp))
+    assert lhs == rhs
+    for i in range(0, prob.n_src, src.tp):
+        for t in range(1, src.tp):
+            assert np.array_equal(sg[i], sg[i + t])
+    assert all(not np.any(a == 0x7FC1) for a in sg)                          # every source row written
+    # gradients on text rows are ignored
+    g2 = [_f2b(x) for x in gf]
+    for j in range(prob.n_dst):
+        sb, _ = prob.forward_map(j)
+        g2[j][sb < 0] = 0x7FC0
+    sg2 = [np.zeros((r, tm.hidden), np.uint16) for r in prob.src_rows()]
+    prob.backward_bf16(g2, sg2)
+    for a, b in zip(sg, sg2):
+        assert np.array_equal(a, b)
+
+
+def test_signalling_nan_stays_nan_when_rounded_to_bf16():
+    """A NaN whose payload lies only in the 16 discarded bits must not round to
+    infinity; the sign is kept."""
+    g = json.load(open(os.path.join(GOLDEN, "bf16_rounding.json")))
+    assert len(g["nan"]) >= 4
+    for case in g["nan"]:
+        got = oracle.f32_bits_to_bf16(int(case["f32_hex"], 16))   # as bits: a Python float would quiet the NaN
+        assert (got & 0x7F80) == 0x7F80 and (got & 0x007F) != 0, case
+        assert (got >> 15) == int(case["sign"]), case
+    # and through the backward fold: a NaN gradient gives a NaN result
+    tm = wl.TokenMap(1, 1, 1, [0], [0], [1])
+    prob = oracle.Problem(wl.Grid(), wl.Grid(tp=2), tm)
+    sg = [np.zeros((1, 1), np.uint16)]
+    prob.backward_bf16([np.array([[0x7FA0]], np.uint16), np.array([[0x3F80]], np.uint16)], sg)
+    assert (int(sg[0][0, 0]) & 0x7F80) == 0x7F80 and (int(sg[0][0, 0]) & 0x7F) != 0
