@@ -156,6 +156,9 @@ int make_tables(hp_plan *p) {
         Seg &d = p->dsegs[i];
         d.src_off = (uint64_t)s.src_row0 * p->row_bytes;
         d.dst_off = (uint64_t)s.dst_row0 * p->row_bytes;
+        if (s.n_rows < 1 || s.n_rows > (int64_t)kMaxSegRows || s.dst_row_stride < 1 ||
+            s.dst_row_stride > (int64_t)UINT32_MAX || s.src_buf > UINT16_MAX || s.dst_buf0 > UINT16_MAX)
+            return HP_ELAYOUT;                                // would not fit the descriptor's fields
         d.n_rows = (uint32_t)s.n_rows;
         d.src_copies = (uint32_t)p->seg_copies[i];
         d.pitch_rows = (uint32_t)s.dst_row_stride;
@@ -343,7 +346,8 @@ int build_host_plan(const hp_layout_t *srcs, int32_t n_edges, const hp_layout_t 
                         if (q.src_buf == seg.src_buf && q.dst_buf0 == seg.dst_buf0 &&
                             q.dst_row_stride == seg.dst_row_stride &&
                             q.src_row0 + q.n_rows == seg.src_row0 &&
-                            q.dst_row0 + q.n_rows * q.dst_row_stride == seg.dst_row0) {
+                            q.dst_row0 + q.n_rows * q.dst_row_stride == seg.dst_row0 &&
+                            q.n_rows + n <= (int64_t)kMaxSegRows) {   // the device descriptor counts rows in 32 bits
                             q.n_rows += n;
                             merged = true;
                         }

@@ -22,6 +22,9 @@ struct alignas(16) Seg {
     uint32_t src_copies;  // identical TP copies of the source rank (buffers src_buf .. +src_copies-1)
 };
 static_assert(sizeof(Seg) == 32, "segment descriptor must stay 32 bytes");
+// Longest run one descriptor can describe; the builder starts a new segment
+// rather than merging past it.
+constexpr uint32_t kMaxSegRows = UINT32_MAX;
 
 // A launch cuts every segment into tiles of 1 KiB << v bytes, one workgroup per
 // tile.  For each variant v the plan keeps first_tile[v][s] = number of tiles of

@@ -388,6 +388,20 @@ def test_size_limits():
     assert q.info.boundary_bytes == ((1 << 20) - 1) << 21 and q.info.n_segments == 3   # chunks 1 and 2 sit back to back on rank 1
     q.set_launch(0, tile_bytes=1024)
     assert q.info.n_tiles == q.info.boundary_bytes // 1024
+    # 4096 all-image samples of 2^21 one-element rows are one contiguous run of 2^33 rows on both
+    # sides; a segment descriptor counts rows in 32 bits, so the run is cut, not truncated
+    B, S = 4096, 1 << 21
+    huge = wl.TokenMap(B, S, 1, list(range(B)), [0] * B, [S] * B)
+    r = hp.hp_plan_create_host(g, g, huge)
+    segs = r.segments()
+    assert r.info.n_rows == B * S == 1 << 33 and len(segs) >= 3
+    assert all(0 < s.n_rows < 1 << 32 for s in segs) and sum(s.n_rows for s in segs) == 1 << 33
+    row = 0
+    for s in segs:                                   # the pieces follow each other without a gap
+        assert (s.src_buf, s.dst_buf0, s.src_row0, s.dst_row0, s.dst_row_stride) == (0, 0, row, row, 1)
+        row += s.n_rows
+    r.set_launch(0, tile_bytes=1024)
+    assert r.info.n_tiles == sum(-(-2 * s.n_rows // 1024) for s in segs)
 
 
 def test_plan_builder_fuzz_under_sanitizers(tmp_path):

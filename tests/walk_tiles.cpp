@@ -57,6 +57,20 @@ int main(int argc, char **argv) {
         hp_plan p;
         if (hp::build_host_plan(&src, 1, &dst, maps.data(), n_maps, &p) != HP_OK) continue;
         ++done;
+        // the device descriptors say what the public segments say (no field narrowed)
+        {
+            int v = -1; uint32_t t = 0;
+            CHECK(p.dsegs.size() == p.segments.size());
+            for (size_t i = 0; i < p.segments.size(); ++i) {
+                t = (uint32_t)i;
+                CHECK((int64_t)p.dsegs[i].n_rows == p.segments[i].n_rows);
+                CHECK((int64_t)p.dsegs[i].pitch_rows == p.segments[i].dst_row_stride);
+                CHECK((int32_t)p.dsegs[i].src_buf == p.segments[i].src_buf);
+                CHECK((int32_t)p.dsegs[i].dst_buf0 == p.segments[i].dst_buf0);
+                CHECK(p.dsegs[i].src_off == (uint64_t)p.segments[i].src_row0 * (uint64_t)p.row_bytes);
+                CHECK(p.dsegs[i].dst_off == (uint64_t)p.segments[i].dst_row0 * (uint64_t)p.row_bytes);
+            }
+        }
         // the tree has to be 64-byte aligned, as it is in the device block
         uint32_t *tree = (uint32_t *)std::aligned_alloc(64, (p.tree.size() * 4 + 63) / 64 * 64 + 64);
         std::copy(p.tree.begin(), p.tree.end(), tree);
