@@ -3,19 +3,31 @@
 
 A step is one pass of the whole hot path over one batch of synthetic input:
 hp_forward (source layout -> destination layout) followed by hp_backward
-(destination gradients -> source layout) on the long-context workload (vision
-DP8 -> LLM TP4 x CP8 zigzag, one 131072-token sample, hidden 5120, ~30 % image
-tokens).  All buffers are resident in HBM before the timed region.  The metric
-is effective HBM GB/s: algorithmic bytes of the two calls divided by their time.
+(destination gradients -> source layout).  All buffers are resident in HBM
+before the timed region.  The metric is effective HBM GB/s: algorithmic bytes of
+the two calls divided by their time.
+
+The headline (`value`) is the long-context workload (vision DP8 -> LLM TP4 x CP8
+zigzag, one 131072-token sample, hidden 5120, ~30 % image tokens).  A default
+run then measures every other workload and variant as well and reports them in
+`configs`, each checked against the CPU oracle.
+
+Other modes:
+  --probe-sweep R:W        rate of a plain R-read : W-write streaming kernel over
+                           launch shapes and tile schedules (hp_probe_stream_ex)
+  --summarize-traffic ...  turn two rocprofv3 counter CSVs of a default run into
+                           profiles/hbm_traffic_<workload>.txt (no GPU needed)
 
 Prints ONE JSON line on stdout; progress goes to stderr.
 """
 from __future__ import annotations
 
 import argparse
+import hashlib
 import json
 import os
 import statistics
+import subprocess
 import sys
 import time
 
@@ -23,35 +35,585 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+KERNEL_SOURCES = ("hp_api.hip", "hp_tile.hpp", "hp_plan.cpp", "hp_plan.hpp")
+WORKLOADS = ["tiny", "colocated4", "colocated4_dense", "long_context", "non_colocated", "large_scale"]
+
+# What a default run reports besides the headline: (label, workload, variant flags).
+EXTRA_CASES = [
+    ("tiny", "tiny", {}),
+    ("colocated4", "colocated4", {}),
+    ("colocated4_dense", "colocated4_dense", {}),
+    ("non_colocated", "non_colocated", {}),
+    ("non_colocated_per_microbatch", "non_colocated", {"per_microbatch": True}),
+    ("large_scale", "large_scale", {}),
+    ("long_context_accumulate", "long_context", {"accumulate": True}),
+    ("long_context_seq_shard", "long_context", {"seq_shard": True}),
+]
 
 
 def log(*a):
     print(*a, file=sys.stderr, flush=True)
 
 
-def read_traffic(workload: str):
+def kernel_source_digest() -> str:
+    """sha256 over the sources the kernels and their launch shapes come from."""
+    h = hashlib.sha256()
+    for name in KERNEL_SOURCES:
+        with open(os.path.join(ROOT, "paper_2605_27678_amd", "csrc", name), "rb") as f:
+            h.update(f.read())
+    return h.hexdigest()
+
+
+def shape_key(shape: dict) -> str:
+    return "{tile_bytes},{block_threads},{waves_per_cu},{nontemporal}".format(**shape)
+
+
+def traffic_label(case: dict) -> str:
+    """Name under which a case's counter summary is filed."""
+    tag = case["workload"]
+    for k in ("accumulate", "seq_shard", "per_microbatch"):
+        if case.get(k):
+            tag += "_" + k
+    if case.get("dtype", "bf16") != "bf16":
+        tag += "_" + case["dtype"]
+    if case.get("row_order", "bsh") != "bsh":
+        tag += "_" + case["row_order"]
+    return tag
+
+
+def read_traffic(label: str):
     """HBM bytes per launch measured with rocprofv3 counters, if a summary for
-    this workload has been committed under profiles/ (key = value lines)."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{workload}.txt")
+    this case has been committed under profiles/ (key = value lines)."""
+    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{label}.txt")
     out = {}
     if os.path.exists(path):
         for line in open(path):
             if "=" in line and not line.lstrip().startswith("#"):
                 k, v = line.split("=", 1)
+                v = v.split("#", 1)[0].strip()
                 try:
-                    out[k.strip()] = float(v.split()[0])
-                except (ValueError, IndexError):
-                    pass
+                    out[k.strip()] = float(v)
+                except ValueError:
+                    out[k.strip()] = v
+        out["_file"] = os.path.relpath(path, ROOT)
     return out
 
+
+def traffic_for(label: str, shapes: dict, dominant: str):
+    """(traffic, bytes per boundary byte, source) for the dominant kernel, or
+    Nones: the committed counter summary is only quoted when it was taken with
+    the kernel sources and the launch shapes that have just run."""
+    t = read_traffic(label)
+    if not t:
+        return None, None, None
+    src = {"file": t["_file"], "head": t.get("head"), "shapes": {"fwd": t.get("shape_fwd"), "bwd": t.get("shape_bwd")},
+           "kernel_sources_sha256": t.get("kernel_sources_sha256")}
+    same = (t.get("kernel_sources_sha256") == kernel_source_digest() and
+            t.get("shape_fwd") == shape_key(shapes["fwd"]) and t.get("shape_bwd") == shape_key(shapes["bwd"]))
+    src["matches_this_run"] = bool(same)
+    if not same:
+        return None, None, src
+    d = "backward" if dominant == "hp_backward_kernel" else "forward"
+    return t.get(f"{d}_bytes_per_launch"), t.get(f"{d}_bytes_per_boundary_byte"), src
+
+
+# --------------------------------------------------------------------------------------
+# one workload / variant
+# --------------------------------------------------------------------------------------
+
+def build_workload(wl, case):
+    from dataclasses import replace
+    w = wl.CONFIGS[case["workload"]]()
+    if case.get("seq_shard"):
+        w = replace(w, dst=replace(w.dst, tp_mode=wl.TP_SEQ_SHARD))
+    if case.get("row_order", "bsh") == "sbh":
+        w = replace(w, dst=replace(w.dst, row_order=wl.ROW_SBH))
+    if case.get("dtype", "bf16") == "f32":
+        w = replace(w, maps=[replace(m, dtype=wl.DT_F32) for m in w.maps])
+    return w
+
+
+def run_case(case: dict, steps: int, warmup: int, oracle_mode: str, tag: str = "bench"):
+    """Builds the plan(s) and resident buffers of one workload variant, times
+    `steps` steps after `warmup`, reads per-launch kernel durations, optionally
+    checks the results against the CPU oracle ("check": all cores, compare only;
+    "time": all cores and one thread, timed), frees everything and returns a
+    dict of results."""
+    import numpy as np
+    import torch
+    import paper_2605_27678_amd as hp
+    from paper_2605_27678_amd import workloads as wl
+
+    dev = "cuda:0"
+    accumulate, f32 = bool(case.get("accumulate")), case.get("dtype", "bf16") == "f32"
+    per_mb, graph, tune = bool(case.get("per_microbatch")), bool(case.get("graph")), bool(case.get("tune"))
+    w = build_workload(wl, case)
+    tdtype = torch.float32 if f32 else torch.bfloat16
+    maps = w.maps
+    H = maps[0].hidden
+    log(f"[{tag}] workload {w.name}: {len(maps)} microbatch(es), hidden {H}, variant "
+        f"{ {k: v for k, v in case.items() if k != 'workload' and v} }")
+
+    # ---- plans and resident buffers (one batched plan, or one plan per microbatch) ----
+    torch.zeros(1, device=dev)                 # HIP context up before the plan build is timed
+    t0 = time.perf_counter()
+    if len(maps) > 1 and not per_mb:
+        plans = [hp.hp_plan_create_batched(w.src, w.dst, maps)]
+    else:
+        plans = [hp.hp_plan_create(w.src, w.dst, m) for m in maps]
+    plan_ms = (time.perf_counter() - t0) * 1e3 / len(plans)
+    seed_of = lambda i, kind, k: w.seed * 100 + i * 7 + kind + k        # kind: 0 source, 50 prefill, 90 gradient
+    sets = []
+    for i, p in enumerate(plans):
+        rows = p.src_rows()
+        src = [wl.random_bf16((r, H), seed_of(i, 0, k), dev).to(tdtype) for k, r in enumerate(rows)]
+        dst = [wl.random_bf16((p.info.dst_rows_per_buf, H), seed_of(i, 50, j), dev).to(tdtype)
+               for j in range(p.info.n_dst_bufs)]
+        grad = [wl.random_bf16((p.info.dst_rows_per_buf, H), seed_of(i, 90, j), dev).to(tdtype)
+                for j in range(p.info.n_dst_bufs)]
+        sgrad = [torch.zeros((r, H), dtype=torch.float32 if accumulate else tdtype, device=dev) for r in rows]
+        ps, pd = p.pointer_arrays(src, dst)
+        pgs, pgd = p.pointer_arrays_accum(sgrad, grad) if accumulate else p.pointer_arrays(sgrad, grad)
+        sets.append(dict(plan=p, src=src, dst=dst, grad=grad, sgrad=sgrad, ps=ps, pd=pd, pgs=pgs, pgd=pgd))
+    fwd_bytes = sum(p.info.fwd_bytes for p in plans)
+    bwd_bytes = sum(p.info.bwd_accum_bytes if accumulate else p.info.bwd_bytes for p in plans)
+    boundary = sum(p.info.boundary_bytes for p in plans)
+    log(f"[{tag}] boundary {boundary / 1e6:.1f} MB, fwd {fwd_bytes / 1e9:.3f} GB, bwd {bwd_bytes / 1e9:.3f} GB, "
+        f"{sum(p.info.n_tiles for p in plans)} tiles, plan build {plan_ms:.2f} ms")
+
+    # The buffers were filled on torch's default stream and the calls below run on a stream of
+    # their own: the fills must have finished first.  (Torch hands the block of a freed temporary
+    # to the next allocation of the same stream, so a kernel of another stream that wrote such a
+    # buffer early would write into a temporary that queued fills still read.)
+    torch.cuda.synchronize()
+    stream = torch.cuda.Stream()
+    n_launch = len(sets)
+
+    # ---- one-time launch-shape search on the resident buffers (not part of a step) ----
+    tune_ms = None
+    if tune:
+        t0 = time.perf_counter()
+        s = sets[0]                      # plans of one workload share their grids: tune one, copy its shapes
+        if accumulate:                   # tune on scratch accumulators: every candidate launch adds into them
+            tmp = [torch.zeros((r, H), dtype=torch.float32, device=dev) for r in s["plan"].src_rows()]
+            s["plan"].tune(s["src"], s["dst"], None, None, stream)
+            s["plan"].tune_accumulate(s["grad"], tmp, stream)
+            del tmp
+        else:
+            s["plan"].tune(s["src"], s["dst"], s["grad"], s["sgrad"], stream)
+        for other in sets[1:]:
+            for d in (0, 1, 2):
+                other["plan"].set_launch(d, **s["plan"].get_launch(d))
+        tune_ms = (time.perf_counter() - t0) * 1e3
+    shapes = {"fwd": sets[0]["plan"].get_launch(0), "bwd": sets[0]["plan"].get_launch(2 if accumulate else 1)}
+    log(f"[{tag}] launch shapes: fwd {shapes['fwd']}  bwd {shapes['bwd']}  (tune {tune_ms} ms)")
+
+    def step():
+        for s in sets:
+            s["plan"].forward_raw(s["ps"], s["pd"], stream)
+        for s in sets:
+            if accumulate:
+                s["plan"].backward_accumulate_raw(s["pgd"], s["pgs"], stream)
+            else:
+                s["plan"].backward_raw(s["pgd"], s["pgs"], stream)
+
+    timed_step = step
+    if graph:
+        step()                                   # first launches outside the capture
+        stream.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g, stream=stream):
+            step()
+        timed_step = g.replay
+    for _ in range(warmup):
+        timed_step()
+    stream.synchronize()
+    torch.cuda.synchronize()
+    rehearsal = 0
+    if n_launch > 1 and not graph:
+        # A step of many launches queues hundreds of dispatches before the closing
+        # synchronisation.  The first device-wide synchronisation after the first
+        # queue that deep has been seen to take 35-40 ms once per process (host
+        # side: the GPU trace shows the kernels back to back and long finished),
+        # so one untimed pass of the same length goes first.
+        rehearsal = steps
+        for _ in range(rehearsal):
+            timed_step()
+        stream.synchronize()
+        torch.cuda.synchronize()
+    # Timed region: EXACTLY `steps` steps between two synchronisations -> `value`.
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        timed_step()
+    enqueue_s = time.perf_counter() - t0       # host time to submit the steps (inside the timed region)
+    stream.synchronize()
+    stream_sync_s = time.perf_counter() - t0
+    torch.cuda.synchronize()
+    total_s = time.perf_counter() - t0
+    log(f"[{tag}] timed region: submitted after {enqueue_s * 1e3:.3f} ms, stream synchronised after "
+        f"{stream_sync_s * 1e3:.3f} ms, device synchronised after {total_s * 1e3:.3f} ms")
+    # The same `steps` steps again, now with a HIP event pair attached to every
+    # launch (stamped by the dispatch itself on the stream it runs on) -> kernel
+    # durations for the roofline.  Kept out of the region above because the
+    # runtime handles event-carrying dispatches one by one, which costs tens of
+    # microseconds per launch when a step is many short launches.
+    hp.hp_profile_enable(2 * n_launch * steps)
+    t0 = time.perf_counter()
+    for _ in range(steps):
+        step()
+    stream.synchronize()
+    torch.cuda.synchronize()
+    total_events_s = time.perf_counter() - t0
+    launches = hp.hp_profile_read(2 * n_launch * steps)
+    hp.hp_profile_enable(0)
+    assert len(launches) == 2 * n_launch * steps
+    per_step = [launches[i * 2 * n_launch:(i + 1) * 2 * n_launch] for i in range(steps)]
+    fwd_ms = [sum(ms for kind, ms in st if kind == 0) for st in per_step]     # kernel time per step
+    bwd_ms = [sum(ms for kind, ms in st if kind != 0) for st in per_step]
+    ms_per_step = total_s * 1e3 / steps
+    value = (fwd_bytes + bwd_bytes) / (total_s / steps) / 1e9
+    f_avg, b_avg = statistics.fmean(fwd_ms), statistics.fmean(bwd_ms)
+    f_med, b_med = statistics.median(fwd_ms), statistics.median(bwd_ms)
+    log(f"[{tag}] kernel time per step: fwd median {f_med:.4f} ms ({fwd_bytes / f_med / 1e6:.0f} GB/s), "
+        f"bwd median {b_med:.4f} ms ({bwd_bytes / b_med / 1e6:.0f} GB/s); wall {ms_per_step:.4f} ms/step "
+        f"({value:.0f} GB/s), of which the host spent {enqueue_s * 1e3 / steps:.4f} submitting; "
+        f"wall with per-launch events {total_events_s * 1e3 / steps:.4f} ms/step")
+
+    # ---- rebuilding the plan at step rate (token maps change every step): warm create + destroy ----
+    t0 = time.perf_counter()
+    for _ in range(20):
+        q = hp.hp_plan_create_batched(w.src, w.dst, maps) if len(plans) == 1 and len(maps) > 1 \
+            else hp.hp_plan_create(w.src, w.dst, maps[0])
+        q.close()
+    plan_rebuild_ms = (time.perf_counter() - t0) * 1e3 / 20
+
+    # ---- roofline of the dominant (slower) kernel: algorithmic bytes per launch / average launch duration ----
+    dominant = "hp_backward_kernel" if b_avg >= f_avg else "hp_forward_kernel"
+    dom_bytes = (bwd_bytes if dominant == "hp_backward_kernel" else fwd_bytes) / n_launch
+    dom_ms = (b_avg if dominant == "hp_backward_kernel" else f_avg) / n_launch
+    traffic, per_boundary, traffic_source = (None, None, None) if (graph or tune) else \
+        traffic_for(traffic_label(case), shapes, dominant)
+    roofline = {
+        "bound": "hbm", "kernel": dominant,
+        "achieved": dom_bytes / dom_ms / 1e6, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
+        "frac": dom_bytes / dom_ms / 1e6 / HBM_PEAK_GBPS,
+        "traffic": traffic,
+        "traffic_source": traffic_source,
+        "bytes_moved_per_boundary_byte": per_boundary,
+        "algorithmic_bytes_per_boundary_byte": dom_bytes * n_launch / boundary if boundary else None,
+        "algorithmic_bytes_per_launch": dom_bytes,
+        "avg_launch_ms": dom_ms,
+    }
+
+    # ---- the CPU oracle on the same workload (first microbatch), host cores of this box ----
+    cpu_baseline = None
+    if oracle_mode in ("check", "time"):
+        from oracle import oracle
+        s, m = sets[0], maps[0]
+        prob = oracle.Problem(w.src, w.dst, m)
+        if f32:
+            host = lambda t: t.cpu().contiguous().numpy()
+            same = lambda a, b: np.array_equal(a.view(np.uint32), b.view(np.uint32))
+            ndt = np.float32
+        else:
+            host = lambda t: t.cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
+            same = np.array_equal
+            ndt = np.uint16
+        n_s, n_d = w.src.n_ranks, w.dst.n_ranks            # microbatch 0 = the first buffers of the set
+        if accumulate:
+            # the accumulators have been added to an unknown number of times: start them from zero
+            # and run one more hp_backward_accumulate, the call the oracle is compared with
+            for t in s["sgrad"]:
+                t.zero_()
+            torch.cuda.synchronize()
+            s["plan"].backward_accumulate_raw(s["pgd"], s["pgs"], stream)
+            stream.synchronize()
+        h_src = [host(t) for t in s["src"][:n_s]]
+        h_grad = [host(t) for t in s["grad"][:n_d]]
+        # The destination prefill ("text embeddings") is drawn again from its seeds rather than read
+        # back from the GPU's output, so a forward that clobbered a text row is seen here too.
+        prefill = lambda: [host(wl.random_bf16((s["plan"].info.dst_rows_per_buf, H), seed_of(0, 50, j), dev).to(tdtype))
+                           for j in range(n_d)]
+        ncores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count()
+        ncores = min(ncores, int(os.environ.get("OMP_NUM_THREADS", ncores)))
+        res = {}
+        for nt in ((ncores, 1) if oracle_mode == "time" else (ncores,)):
+            h_dst = prefill()
+            h_sg = [np.zeros((r, H), np.float32 if accumulate else ndt) for r in prob.src_rows()]
+            oracle.set_threads(nt)
+            t0 = time.perf_counter()
+            prob.forward(h_src, h_dst)
+            t1 = time.perf_counter()
+            if accumulate:
+                prob.backward_accumulate(h_grad, h_sg)
+            elif f32:
+                prob.backward_f32(h_grad, h_sg)
+            else:
+                prob.backward_bf16(h_grad, h_sg)
+            t2 = time.perf_counter()
+            res[nt] = (t1 - t0, t2 - t1)
+            log(f"[{tag}] oracle {nt} thread(s): fwd {t1 - t0:.3f} s, bwd {t2 - t1:.3f} s")
+        p0 = s["plan"].info
+        ob = (1 + p0.dst_copies) * m.n_rows * p0.row_bytes + (
+            p0.dst_copies * m.n_rows * p0.row_bytes + p0.src_copies * 2 * m.n_rows * H * 4 if accumulate
+            else (p0.dst_copies + p0.src_copies) * m.n_rows * p0.row_bytes)
+        cpu_baseline = {
+            "value": ob / sum(res[ncores]) / 1e9, "unit": "GB/s", "cores": ncores, "kind": "oracle",
+            "sample": f"one full forward+backward pass of {w.name} (microbatch 0), {ob / 1e9:.2f} GB algorithmic",
+            "fwd_s": res[ncores][0], "bwd_s": res[ncores][1],
+        }
+        if 1 in res and ncores != 1:
+            cpu_baseline.update({"one_thread_value": ob / sum(res[1]) / 1e9, "one_thread_fwd_s": res[1][0],
+                                 "one_thread_bwd_s": res[1][1]})
+        # The GPU results of the last step must equal what the oracle computed from the same inputs:
+        # the source gradients everywhere, the destination buffers on EVERY row (image rows moved,
+        # text rows as prefilled).
+        if accumulate:                                         # binary32 accumulators whatever the gradients' dtype
+            ok_b = all(np.array_equal(t.cpu().numpy().view(np.uint32), h.view(np.uint32))
+                       for t, h in zip(s["sgrad"][:n_s], h_sg))
+        else:
+            ok_b = all(same(host(t), h) for t, h in zip(s["sgrad"][:n_s], h_sg))
+        ok_f = True
+        for j, (t, h) in enumerate(zip(s["dst"][:n_d], h_dst)):
+            got = host(t)
+            if not same(got, h):
+                ok_f = False
+                bad = (got != h).reshape(got.shape[0], -1).any(axis=1)
+                is_img = prob.forward_map(j)[0] >= 0
+                log(f"[{tag}] forward differs from the oracle in destination buffer {j}: {int(bad.sum())} rows "
+                    f"({int((bad & is_img).sum())} image rows, {int((bad & ~is_img).sum())} text rows), first row "
+                    f"{int(np.nonzero(bad)[0][0])}")
+        cpu_baseline["gpu_matches_oracle"] = bool(ok_b and ok_f)
+        cpu_baseline["gpu_matches_oracle_forward"] = bool(ok_f)
+        cpu_baseline["gpu_matches_oracle_backward"] = bool(ok_b)
+        log(f"[{tag}] GPU results equal the oracle's: forward {ok_f}, backward {ok_b}")
+        del h_src, h_grad, h_dst, h_sg
+
+    p0i = sets[0]["plan"].info
+    out = {
+        "value": value, "ms_per_step": ms_per_step,
+        "config": {"workload": w.name, "src": f"tp{w.src.tp}dp{w.src.dp}",
+                   "dst": f"tp{w.dst.tp}cp{w.dst.cp}dp{w.dst.dp}",
+                   "batch": maps[0].batch, "seq": maps[0].seq, "hidden": H, "microbatches": len(maps),
+                   "tp_mode": "seq_shard" if case.get("seq_shard") else "replicate",
+                   "row_order": case.get("row_order", "bsh"),
+                   "backward": "accumulate_f32" if accumulate else "overwrite",
+                   "accumulate_dtype": "f32", "launches_per_direction": n_launch, "launch_shapes": shapes, "tuned": tune,
+                   "submission": "hip_graph_replay" if graph else "eager",
+                   "image_rows": int(sum(m.n_rows for m in maps)), "boundary_bytes": boundary,
+                   "tiles_fwd": [int(p.info.n_tiles) for p in plans][:4],
+                   },
+        "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
+        "forward": {"bytes": fwd_bytes, "median_ms": f_med, "min_ms": min(fwd_ms), "max_ms": max(fwd_ms),
+                    "GBps": fwd_bytes / f_med / 1e6, "pct_of_hbm_peak": fwd_bytes / f_med / 1e6 / HBM_PEAK_GBPS * 100},
+        "backward": {"bytes": bwd_bytes, "median_ms": b_med, "min_ms": min(bwd_ms), "max_ms": max(bwd_ms),
+                     "GBps": bwd_bytes / b_med / 1e6, "pct_of_hbm_peak": bwd_bytes / b_med / 1e6 / HBM_PEAK_GBPS * 100},
+        "ms_per_step_with_kernel_events": total_events_s * 1e3 / steps,
+        "host_submit_ms_per_step": enqueue_s * 1e3 / steps,
+        "ms_per_step_to_stream_sync": stream_sync_s * 1e3 / steps,
+        "untimed_rehearsal_steps": rehearsal,
+        "plan_build_ms": plan_ms, "plan_rebuild_ms": plan_rebuild_ms, "plan_tune_ms": tune_ms,
+        "roofline": roofline,
+        "cpu_baseline": cpu_baseline,
+        "_dims": {"dst_copies": p0i.dst_copies, "src_copies": p0i.src_copies, "boundary": boundary, "fwd_bytes": fwd_bytes},
+    }
+    for s in sets:
+        s["plan"].close()
+    del sets, plans
+    torch.cuda.synchronize()
+    torch.cuda.empty_cache()
+    return out
+
+
+def compact(label: str, r: dict) -> dict:
+    """One entry of the `configs` list."""
+    c = r["config"]
+    cb = r["cpu_baseline"] or {}
+    return {
+        "name": label, "workload": c["workload"], "tp_mode": c["tp_mode"], "backward": c["backward"],
+        "launches_per_direction": c["launches_per_direction"], "launch_shapes": c["launch_shapes"],
+        "boundary_bytes": c["boundary_bytes"],
+        "fwd_bytes": r["forward"]["bytes"], "bwd_bytes": r["backward"]["bytes"],
+        "fwd_median_ms": r["forward"]["median_ms"], "bwd_median_ms": r["backward"]["median_ms"],
+        "fwd_GBps": r["forward"]["GBps"], "bwd_GBps": r["backward"]["GBps"],
+        "fwd_frac": r["forward"]["GBps"] / HBM_PEAK_GBPS, "bwd_frac": r["backward"]["GBps"] / HBM_PEAK_GBPS,
+        "value_GBps": r["value"], "ms_per_step": r["ms_per_step"],
+        "traffic": r["roofline"]["traffic"], "traffic_kernel": r["roofline"]["kernel"],
+        "bytes_moved_per_boundary_byte": r["roofline"]["bytes_moved_per_boundary_byte"],
+        "gpu_matches_oracle": cb.get("gpu_matches_oracle"),
+        "oracle_GBps": cb.get("value"), "oracle_cores": cb.get("cores"),
+    }
+
+
+# --------------------------------------------------------------------------------------
+# probe sweep
+# --------------------------------------------------------------------------------------
+
+def probe_sweep(args) -> int:
+    import torch
+    import paper_2605_27678_amd as hp
+    if not torch.cuda.is_available():
+        log("bench.py: no GPU visible")
+        return 3
+    torch.cuda.set_device(0)
+    torch.zeros(1, device="cuda:0")
+    n_read, n_write = (int(x) for x in args.probe_sweep.split(":"))
+    nt = args.probe_nontemporal if args.probe_nontemporal is not None else (3 if n_read > n_write else 2)
+    nbytes = args.probe_mb * 1000000 // 4096 * 4096
+    caps = [int(c) for c in args.probe_caps.split(",")]
+    shapes = [tuple(int(v) for v in s.split("x")) for s in args.probe_shapes.split(",")]
+    schedules = args.probe_schedules.split(",")
+    tables = {}
+    for sched in schedules:
+        log(f"{n_read}R:{n_write}W, {nbytes} B per array, nontemporal={nt}, schedule {sched}; "
+            f"GB/s by resident waves per CU (32 = no cap)")
+        log("tile_bytes block chunks/lane | " + " ".join(f"{c:>6d}" for c in caps))
+        rows = []
+        for tile, block in shapes:
+            row = []
+            for cap in caps:
+                if cap < 2 * (block // 64):
+                    row.append(None)
+                    continue
+                shape = dict(tile_bytes=tile, block_threads=block, waves_per_cu=0 if cap >= 32 else cap, nontemporal=nt)
+                row.append(hp.hp_probe_stream_ex(n_read, n_write, nbytes, shape, sched))
+            log(f"{tile:10d} {block:5d} {tile // 16 // block:11d} | " +
+                " ".join("     -" if v is None else f"{v:6.0f}" for v in row))
+            rows.append({"tile_bytes": tile, "block_threads": block, "GBps": row})
+        best = max((v, r["tile_bytes"], r["block_threads"], c) for r in rows for v, c in zip(r["GBps"], caps) if v)
+        log(f"best: {best[0]:.0f} GB/s at tile {best[1]}, block {best[2]}, cap {best[3]}")
+        tables[sched] = {"rows": rows, "best": {"GBps": best[0], "tile_bytes": best[1], "block_threads": best[2],
+                                                "waves_per_cu": best[3]}}
+    print(json.dumps({"probe": f"{n_read}R:{n_write}W", "bytes_per_array": nbytes, "nontemporal": nt, "caps": caps,
+                      "schedules": tables}), flush=True)
+    return 0
+
+
+# --------------------------------------------------------------------------------------
+# counter summaries (no GPU): rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE CSVs -> profiles/hbm_traffic_<case>.txt
+# --------------------------------------------------------------------------------------
+
+def summarize_traffic(args) -> int:
+    """Reads the counter_collection CSVs of two rocprofv3 passes over a default
+    bench.py run (one with FETCH_SIZE, one with WRITE_SIZE), finds the dispatches
+    of every case by kernel name and grid size, calibrates both counters on the
+    run's plain device copy and writes one summary per case."""
+    import csv
+    import paper_2605_27678_amd as hp
+    from paper_2605_27678_amd import workloads as wl
+
+    def load(path, counter):
+        rows = []
+        with open(path, newline="") as f:
+            for r in csv.DictReader(f):
+                if r.get("Counter_Name") == counter:
+                    rows.append((r["Kernel_Name"], int(r["Grid_Size"]), int(r["Workgroup_Size"]), float(r["Counter_Value"])))
+        return rows
+
+    fetch, write = load(args.summarize_traffic[0], "FETCH_SIZE"), load(args.summarize_traffic[1], "WRITE_SIZE")
+    copy_bytes = int(args.copy_bytes)
+
+    def mean_of(rows, pred):
+        v = [x[3] for x in rows if pred(x)]
+        return (sum(v) / len(v), len(v), min(v), max(v)) if v else (None, 0, None, None)
+
+    # calibration: the device copy bench.py times moves copy_bytes each way per dispatch
+    is_copy = lambda x: "copyBuffer" in x[0]
+    big = max((x[3] for x in write if is_copy(x)), default=None)
+    if big is None:
+        log("no device-copy dispatches found in the WRITE_SIZE pass")
+        return 1
+    cw = mean_of(write, lambda x: is_copy(x) and x[3] > 0.9 * big)
+    bigf = max(x[3] for x in fetch if is_copy(x))
+    cf = mean_of(fetch, lambda x: is_copy(x) and x[3] > 0.9 * bigf)
+    fetch_scale = copy_bytes / 1024.0 / cf[0]
+    write_scale = copy_bytes / 1024.0 / cw[0]
+    try:
+        head = subprocess.run(["git", "rev-parse", "--short", "HEAD"], cwd=ROOT, capture_output=True, text=True).stdout.strip()
+    except OSError:
+        head = ""
+    digest = kernel_source_digest()
+    cases = [("long_context", "long_context", {})] + [c for c in EXTRA_CASES if not c[2].get("per_microbatch")]
+    written = []
+    for label, workload, flags in cases:
+        case = dict(workload=workload, **flags)
+        w = build_workload(wl, case)
+        plan = hp.hp_plan_create_batched(w.src, w.dst, w.maps, host_only=True) if len(w.maps) > 1 \
+            else hp.hp_plan_create_host(w.src, w.dst, w.maps[0])
+        info = plan.info
+        acc = bool(flags.get("accumulate"))
+        sf, sb = plan.get_launch(0), plan.get_launch(2 if acc else 1)
+        grid = {}
+        for d, shp in ((0, sf), (2 if acc else 1, sb)):
+            q = hp.hp_plan_create_batched(w.src, w.dst, w.maps, host_only=True) if len(w.maps) > 1 \
+                else hp.hp_plan_create_host(w.src, w.dst, w.maps[0])
+            q.set_launch(0, tile_bytes=shp["tile_bytes"])          # n_tiles is reported for direction 0's tile size
+            grid[d] = q.info.n_tiles * shp["block_threads"]
+            q.close()
+        fb = info.fwd_bytes
+        bb = info.bwd_accum_bytes if acc else info.bwd_bytes
+        res = {}
+        for d, name, g in ((0, "hp_forward_kernel", grid[0]), (1, "hp_backward_kernel", grid[2 if acc else 1])):
+            pred = lambda x, name=name, g=g: name in x[0] and x[1] == g
+            f, w_ = mean_of(fetch, pred), mean_of(write, pred)
+            if f[0] is None or w_[0] is None:
+                res = None
+                break
+            res[d] = (f, w_)
+        if res is None:
+            log(f"{label}: no dispatches with the expected grid sizes {grid} - skipped")
+            continue
+        tag = traffic_label(case)
+        path = os.path.join(ROOT, "profiles", f"hbm_traffic_{tag}.txt")
+        (ff, fw), (bf, bw) = res[0], res[1]
+        f_bytes = ff[0] * 1024 * fetch_scale + fw[0] * 1024 * write_scale
+        b_bytes = bf[0] * 1024 * fetch_scale + bw[0] * 1024 * write_scale
+        with open(path, "w") as out:
+            out.write(
+                f"# HBM traffic per launch of the two kernels on case {tag} (workload {workload}, variant {flags or 'plain'}),\n"
+                "# from two rocprofv3 counter passes of the same committed command (run from /tmp, TMPDIR=/tmp,\n"
+                "# repository at $R; the default run measures every case, this file keeps this case's dispatches,\n"
+                "# found by kernel name and grid size):\n#\n"
+                "#   rocprofv3 --pmc FETCH_SIZE -f csv -d $R/gpurun_out/prof_fetch -o bench -- python3 $R/bench.py --no-cpu-baseline --steps 3 --warmup 1\n"
+                "#   rocprofv3 --pmc WRITE_SIZE -f csv -d $R/gpurun_out/prof_write -o bench -- python3 $R/bench.py --no-cpu-baseline --steps 3 --warmup 1\n"
+                "#   python3 bench.py --summarize-traffic <fetch pass>/bench_counter_collection.csv <write pass>/bench_counter_collection.csv\n#\n"
+                f"# Raw counter readings (KiB per dispatch, mean; dispatches; min..max):\n"
+                f"#   hp_forward_kernel   FETCH_SIZE {ff[0]:.1f} ({ff[1]}; {ff[2]:.1f}..{ff[3]:.1f})   WRITE_SIZE {fw[0]:.1f} ({fw[1]}; {fw[2]:.1f}..{fw[3]:.1f})\n"
+                f"#   hp_backward_kernel  FETCH_SIZE {bf[0]:.1f} ({bf[1]}; {bf[2]:.1f}..{bf[3]:.1f})   WRITE_SIZE {bw[0]:.1f} ({bw[1]}; {bw[2]:.1f}..{bw[3]:.1f})\n#\n"
+                f"# Calibration on the plain device copy bench.py times in the same runs ({copy_bytes} B each way per\n"
+                f"# dispatch): FETCH_SIZE reads {cf[0]:.1f} KiB ({cf[1]} dispatches), WRITE_SIZE {cw[0]:.1f} KiB ({cw[1]}).\n"
+                f"fetch_scale = {fetch_scale:.4f}\nwrite_scale = {write_scale:.4f}\n#\n"
+                "# What ran: the commit, a digest of the kernel sources, and the launch shapes\n"
+                "# (tile_bytes,block_threads,waves_per_cu,nontemporal).  bench.py quotes the figures below only\n"
+                "# when its own digest and launch shapes equal these.\n"
+                f"head = {head}\nkernel_sources_sha256 = {digest}\nshape_fwd = {shape_key(sf)}\nshape_bwd = {shape_key(sb)}\n#\n"
+                "# Scaled traffic, bytes per launch (algorithmic bytes beside it):\n"
+                f"forward_fetch_bytes = {ff[0] * 1024 * fetch_scale:.0f}\nforward_write_bytes = {fw[0] * 1024 * write_scale:.0f}\n"
+                f"forward_bytes_per_launch = {f_bytes:.0f}     # algorithmic {fb}; x{f_bytes / fb:.4f}\n"
+                f"backward_fetch_bytes = {bf[0] * 1024 * fetch_scale:.0f}\nbackward_write_bytes = {bw[0] * 1024 * write_scale:.0f}\n"
+                f"backward_bytes_per_launch = {b_bytes:.0f}     # algorithmic {bb}; x{b_bytes / bb:.4f}\n#\n"
+                f"# Bytes moved per boundary byte (boundary = {info.boundary_bytes} B); algorithmic: forward "
+                f"{fb / info.boundary_bytes:.4f}, backward {bb / info.boundary_bytes:.4f}\n"
+                f"forward_bytes_per_boundary_byte = {f_bytes / info.boundary_bytes:.4f}\n"
+                f"backward_bytes_per_boundary_byte = {b_bytes / info.boundary_bytes:.4f}\n")
+        plan.close()
+        written.append(os.path.relpath(path, ROOT))
+        log(f"{tag}: forward x{f_bytes / fb:.4f}, backward x{b_bytes / bb:.4f} of the algorithmic bytes -> {written[-1]}")
+    print(json.dumps({"written": written, "fetch_scale": fetch_scale, "write_scale": write_scale, "head": head}))
+    return 0
+
+
+# --------------------------------------------------------------------------------------
 
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
     ap.add_argument("--steps", type=int, default=15)
     ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="long_context",
-                    choices=["tiny", "colocated4", "colocated4_dense", "long_context", "non_colocated", "large_scale"])
+    ap.add_argument("--workload", default=None, choices=WORKLOADS,
+                    help="measure this workload only (default: long_context as the headline, then every other "
+                         "workload and variant in `configs`)")
+    ap.add_argument("--headline-only", action="store_true", help="skip the `configs` list of a default run")
     ap.add_argument("--graph", action="store_true",
                     help="record one step into a HIP graph and time its replays (wall clock); kernel "
                          "durations still come from eager launches carrying events")
@@ -70,16 +632,33 @@ def main() -> int:
                     help="one plan and one launch per microbatch instead of one batched plan")
     ap.add_argument("--option", action="append", default=[], metavar="KEY=INT",
                     help="library tuning knob, e.g. tile_bytes_fwd=4096 (see hp_set_option)")
+    ap.add_argument("--probe-sweep", metavar="R:W", default=None,
+                    help="instead of the benchmark: GB/s of a plain R-read : W-write streaming kernel by launch shape "
+                         "and tile schedule")
+    ap.add_argument("--probe-mb", type=int, default=400, help="megabytes per array of the probe")
+    ap.add_argument("--probe-nontemporal", type=int, default=None, help="bit 0 loads, bit 1 stores (default 2 if W>=R else 3)")
+    ap.add_argument("--probe-caps", default="4,6,8,12,16,24,32", help="resident-wave caps to sweep (32 = none)")
+    ap.add_argument("--probe-shapes", default="1024x64,2048x64,2048x128,4096x64,4096x128,4096x256,8192x64,8192x128,"
+                                              "8192x256,32768x64,32768x256,32768x1024",
+                    help="tile_bytes x block_threads pairs to sweep")
+    ap.add_argument("--probe-schedules", default="oneshot,xcd_chunked,persistent,persistent_xcd")
+    ap.add_argument("--summarize-traffic", nargs=2, metavar=("FETCH_CSV", "WRITE_CSV"), default=None,
+                    help="write profiles/hbm_traffic_<case>.txt from two rocprofv3 counter CSVs of a default run")
+    ap.add_argument("--copy-bytes", default=str(1027558400),
+                    help="bytes the calibration copy moves each way per dispatch (half the headline's forward bytes)")
     args = ap.parse_args()
 
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
         log("bench.py: this build runs on ONE GPU: every source and destination rank is a buffer "
             "in one GPU's HBM and there is no multi-GPU path. Re-run with --gpus 1.")
         return 2
+    if args.summarize_traffic:
+        return summarize_traffic(args)
+    if args.probe_sweep:
+        return probe_sweep(args)
 
     import torch
     import paper_2605_27678_amd as hp
-    from paper_2605_27678_amd import workloads as wl
 
     if not torch.cuda.is_available():
         log("bench.py: no GPU visible; the transform has no CPU path")
@@ -90,149 +669,18 @@ def main() -> int:
         key, val = kv.split("=", 1)
         hp.hp_set_option(key, int(val))
 
-    from dataclasses import replace
-    w = wl.CONFIGS[args.workload]()
-    if args.seq_shard:
-        w = replace(w, dst=replace(w.dst, tp_mode=wl.TP_SEQ_SHARD))
-    if args.row_order == "sbh":
-        w = replace(w, dst=replace(w.dst, row_order=wl.ROW_SBH))
-    if args.dtype == "f32":
-        w = replace(w, maps=[replace(m, dtype=wl.DT_F32) for m in w.maps])
-    tdtype = torch.float32 if args.dtype == "f32" else torch.bfloat16
-    maps = w.maps
-    H = maps[0].hidden
-    log(f"[bench] workload {w.name}: {len(maps)} microbatch(es), hidden {H}")
-
-    # ---- plans and resident buffers (one batched plan, or one plan per microbatch) ----
-    torch.zeros(1, device=dev)                 # HIP context up before the plan build is timed
-    t0 = time.perf_counter()
-    if len(maps) > 1 and not args.per_microbatch:
-        plans = [hp.hp_plan_create_batched(w.src, w.dst, maps)]
-    else:
-        plans = [hp.hp_plan_create(w.src, w.dst, m) for m in maps]
-    plan_ms = (time.perf_counter() - t0) * 1e3 / len(plans)
-    sets = []
-    for i, p in enumerate(plans):
-        rows = p.src_rows()
-        src = [wl.random_bf16((r, H), w.seed * 100 + i * 7 + k, dev).to(tdtype) for k, r in enumerate(rows)]
-        dst = [wl.random_bf16((p.info.dst_rows_per_buf, H), w.seed * 100 + 50 + j, dev).to(tdtype)
-               for j in range(p.info.n_dst_bufs)]
-        grad = [wl.random_bf16((p.info.dst_rows_per_buf, H), w.seed * 100 + 90 + j, dev).to(tdtype)
-                for j in range(p.info.n_dst_bufs)]
-        sgrad = [torch.zeros((r, H), dtype=torch.float32 if args.accumulate else tdtype, device=dev) for r in rows]
-        ps, pd = p.pointer_arrays(src, dst)
-        pgs, pgd = p.pointer_arrays_accum(sgrad, grad) if args.accumulate else p.pointer_arrays(sgrad, grad)
-        sets.append(dict(plan=p, src=src, dst=dst, grad=grad, sgrad=sgrad, ps=ps, pd=pd, pgs=pgs, pgd=pgd))
-    fwd_bytes = sum(p.info.fwd_bytes for p in plans)
-    bwd_bytes = sum(p.info.bwd_accum_bytes if args.accumulate else p.info.bwd_bytes for p in plans)
-    boundary = sum(p.info.boundary_bytes for p in plans)
-    log(f"[bench] boundary {boundary / 1e6:.1f} MB, fwd {fwd_bytes / 1e9:.3f} GB, bwd {bwd_bytes / 1e9:.3f} GB, "
-        f"{sum(p.info.n_tiles for p in plans)} tiles, plan build {plan_ms:.2f} ms")
-
+    variant = dict(accumulate=args.accumulate, seq_shard=args.seq_shard, per_microbatch=args.per_microbatch,
+                   dtype=args.dtype, row_order=args.row_order, graph=args.graph, tune=args.tune)
+    single = args.workload is not None or any((args.accumulate, args.seq_shard, args.per_microbatch, args.graph,
+                                               args.tune, args.dtype != "bf16", args.row_order != "bsh",
+                                               args.headline_only, bool(args.option)))
+    head_case = dict(workload=args.workload or "long_context", **variant)
+    r = run_case(head_case, args.steps, args.warmup, "none" if args.no_cpu_baseline else "time")
+    dims = r.pop("_dims")
     stream = torch.cuda.Stream()
-    n_launch = len(sets)
-
-    # ---- one-time launch-shape search on the resident buffers (not part of a step) ----
-    tune_ms = None
-    if args.tune:
-        t0 = time.perf_counter()
-        s = sets[0]                      # plans of one workload share their grids: tune one, copy its shapes
-        if args.accumulate:              # tune on scratch accumulators: every candidate launch adds into them
-            tmp = [torch.zeros((r, H), dtype=torch.float32, device=dev) for r in s["plan"].src_rows()]
-            s["plan"].tune(s["src"], s["dst"], None, None, stream)
-            s["plan"].tune_accumulate(s["grad"], tmp, stream)
-            del tmp
-        else:
-            s["plan"].tune(s["src"], s["dst"], s["grad"], s["sgrad"], stream)
-        for other in sets[1:]:
-            for d in (0, 1, 2):
-                other["plan"].set_launch(d, **s["plan"].get_launch(d))
-        tune_ms = (time.perf_counter() - t0) * 1e3
-    shapes = {"fwd": sets[0]["plan"].get_launch(0), "bwd": sets[0]["plan"].get_launch(2 if args.accumulate else 1)}
-    log(f"[bench] launch shapes: fwd {shapes['fwd']}  bwd {shapes['bwd']}  (tune {tune_ms} ms)")
-
-    def step():
-        for s in sets:
-            s["plan"].forward_raw(s["ps"], s["pd"], stream)
-        for s in sets:
-            if args.accumulate:
-                s["plan"].backward_accumulate_raw(s["pgd"], s["pgs"], stream)
-            else:
-                s["plan"].backward_raw(s["pgd"], s["pgs"], stream)
-
-    timed_step = step
-    if args.graph:
-        step()                                   # first launches outside the capture
-        stream.synchronize()
-        graph = torch.cuda.CUDAGraph()
-        with torch.cuda.graph(graph, stream=stream):
-            step()
-        timed_step = graph.replay
-    for _ in range(args.warmup):
-        timed_step()
-    stream.synchronize()
-    torch.cuda.synchronize()
-    rehearsal = 0
-    if n_launch > 1 and not args.graph:
-        # A step of many launches queues hundreds of dispatches before the closing
-        # synchronisation.  The first device-wide synchronisation after the first
-        # queue that deep has been seen to take 35-40 ms once per process (host
-        # side: the GPU trace shows the kernels back to back and long finished),
-        # so one untimed pass of the same length goes first.
-        rehearsal = args.steps
-        for _ in range(rehearsal):
-            timed_step()
-        stream.synchronize()
-        torch.cuda.synchronize()
-    # Timed region: EXACTLY `steps` steps between two synchronisations -> `value`.
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        timed_step()
-    enqueue_s = time.perf_counter() - t0       # host time to submit the steps (inside the timed region)
-    stream.synchronize()
-    stream_sync_s = time.perf_counter() - t0
-    torch.cuda.synchronize()
-    total_s = time.perf_counter() - t0
-    log(f"[bench] timed region: submitted after {enqueue_s * 1e3:.3f} ms, stream synchronised after "
-        f"{stream_sync_s * 1e3:.3f} ms, device synchronised after {total_s * 1e3:.3f} ms")
-    # The same `steps` steps again, now with a HIP event pair attached to every
-    # launch (stamped by the dispatch itself on the stream it runs on) -> kernel
-    # durations for the roofline.  Kept out of the region above because the
-    # runtime handles event-carrying dispatches one by one, which costs tens of
-    # microseconds per launch when a step is many short launches.
-    hp.hp_profile_enable(2 * n_launch * args.steps)
-    t0 = time.perf_counter()
-    for _ in range(args.steps):
-        step()
-    stream.synchronize()
-    torch.cuda.synchronize()
-    total_events_s = time.perf_counter() - t0
-    launches = hp.hp_profile_read(2 * n_launch * args.steps)
-    hp.hp_profile_enable(0)
-    assert len(launches) == 2 * n_launch * args.steps
-    per_step = [launches[i * 2 * n_launch:(i + 1) * 2 * n_launch] for i in range(args.steps)]
-    fwd_ms = [sum(ms for kind, ms in st if kind == 0) for st in per_step]     # kernel time per step
-    bwd_ms = [sum(ms for kind, ms in st if kind != 0) for st in per_step]
-    ms_per_step = total_s * 1e3 / args.steps
-    value = (fwd_bytes + bwd_bytes) / (total_s / args.steps) / 1e9
-    f_avg, b_avg = statistics.fmean(fwd_ms), statistics.fmean(bwd_ms)
-    f_med, b_med = statistics.median(fwd_ms), statistics.median(bwd_ms)
-    log(f"[bench] kernel time per step: fwd median {f_med:.4f} ms ({fwd_bytes / f_med / 1e6:.0f} GB/s), "
-        f"bwd median {b_med:.4f} ms ({bwd_bytes / b_med / 1e6:.0f} GB/s); wall {ms_per_step:.4f} ms/step "
-        f"({value:.0f} GB/s), of which the host spent {enqueue_s * 1e3 / args.steps:.4f} submitting; "
-        f"wall with per-launch events {total_events_s * 1e3 / args.steps:.4f} ms/step")
-
-    # ---- rebuilding the plan at step rate (token maps change every step): warm create + destroy ----
-    t0 = time.perf_counter()
-    for _ in range(20):
-        q = hp.hp_plan_create_batched(w.src, w.dst, maps) if len(plans) == 1 and len(maps) > 1 \
-            else hp.hp_plan_create(w.src, w.dst, maps[0])
-        q.close()
-    plan_rebuild_ms = (time.perf_counter() - t0) * 1e3 / 20
-    log(f"[bench] plan create+destroy, warm: {plan_rebuild_ms:.3f} ms")
 
     # ---- plain device copy of the same byte count: practical ceiling ----
-    n_copy = (fwd_bytes // 2) // 2
+    n_copy = (dims["fwd_bytes"] // 2) // 2
     a = torch.empty(n_copy, dtype=torch.bfloat16, device=dev)
     b = torch.empty_like(a)
     with torch.cuda.stream(stream):
@@ -249,133 +697,37 @@ def main() -> int:
     log(f"[bench] plain copy of {2 * n_copy * 2 / 1e9:.2f} GB traffic: {copy_gbps:.0f} GB/s")
 
     # ---- the access pattern's own ceiling: plain linear arrays, same lanes and launch search, no tables ----
-    p0i = sets[0]["plan"].info
-    arr = max(int(min(boundary, 1 << 30)) // 4096 * 4096, 1 << 20)
-    ceil_f, shape_f = hp.hp_probe_stream(1, min(p0i.dst_copies, 8), arr)
-    ceil_b, shape_b = hp.hp_probe_stream(min(p0i.dst_copies, 8), min(p0i.src_copies, 8), arr)   # (overwriting backward)
-    log(f"[bench] pattern ceilings: 1R:{p0i.dst_copies}W {ceil_f:.0f} GB/s {shape_f}; "
-        f"{p0i.dst_copies}R:{p0i.src_copies}W {ceil_b:.0f} GB/s {shape_b}")
+    arr = max(int(min(dims["boundary"], 1 << 30)) // 4096 * 4096, 1 << 20)
+    ceil_f, shape_f = hp.hp_probe_stream(1, min(dims["dst_copies"], 8), arr)
+    ceil_b, shape_b = hp.hp_probe_stream(min(dims["dst_copies"], 8), min(dims["src_copies"], 8), arr)   # (overwriting backward)
+    log(f"[bench] pattern ceilings: 1R:{dims['dst_copies']}W {ceil_f:.0f} GB/s {shape_f}; "
+        f"{dims['dst_copies']}R:{dims['src_copies']}W {ceil_b:.0f} GB/s {shape_b}")
 
-    # ---- roofline of the dominant (slower) kernel: algorithmic bytes per launch / average launch duration ----
-    dominant = "hp_backward_kernel" if b_avg >= f_avg else "hp_forward_kernel"
-    dom_bytes = (bwd_bytes if dominant == "hp_backward_kernel" else fwd_bytes) / n_launch
-    dom_ms = (b_avg if dominant == "hp_backward_kernel" else f_avg) / n_launch
-    # the committed counter summary describes the workload's plain configuration only
-    plain = args.dtype == "bf16" and not (args.accumulate or args.seq_shard or args.per_microbatch) \
-        and args.row_order == "bsh"
-    traffic = read_traffic(w.name) if plain else {}
-    tkey = "backward_bytes_per_launch" if dominant == "hp_backward_kernel" else "forward_bytes_per_launch"
-    roofline = {
-        "bound": "hbm", "kernel": dominant,
-        "achieved": dom_bytes / dom_ms / 1e6, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-        "frac": dom_bytes / dom_ms / 1e6 / HBM_PEAK_GBPS,
-        "traffic": traffic.get(tkey),
-        "bytes_moved_per_boundary_byte": traffic.get(tkey.replace("_bytes_per_launch", "_bytes_per_boundary_byte")),
-        "algorithmic_bytes_per_boundary_byte": dom_bytes * n_launch / boundary if boundary else None,
-        "algorithmic_bytes_per_launch": dom_bytes,
-        "avg_launch_ms": dom_ms,
-    }
-
-    # ---- the CPU oracle on the same workload, host cores of this machine ----
-    cpu_baseline = None
-    if not args.no_cpu_baseline:
-        from oracle import oracle
-        import numpy as np
-        log("[bench] timing the CPU oracle on the same workload (first microbatch) ...")
-        s, m = sets[0], maps[0]
-        prob = oracle.Problem(w.src, w.dst, m)
-        if args.dtype == "f32":
-            host = lambda t: t.cpu().contiguous().numpy()
-            same = lambda a, b: np.array_equal(a.view(np.uint32), b.view(np.uint32))
-            ndt = np.float32
-        else:
-            host = lambda t: t.cpu().contiguous().view(torch.int16).numpy().view(np.uint16)
-            same = np.array_equal
-            ndt = np.uint16
-        n_s, n_d = w.src.n_ranks, w.dst.n_ranks            # microbatch 0 = the first buffers of the set
-        if args.accumulate:
-            # the accumulators have been added to an unknown number of times: start them from zero
-            # and run one more hp_backward_accumulate, the call the oracle is compared with
-            for t in s["sgrad"]:
-                t.zero_()
-            torch.cuda.synchronize()
-            s["plan"].backward_accumulate_raw(s["pgd"], s["pgs"], stream)
-            stream.synchronize()
-        h_src = [host(t) for t in s["src"][:n_s]]
-        h_dst = [host(t) for t in s["dst"][:n_d]]
-        h_grad = [host(t) for t in s["grad"][:n_d]]
-        ncores = len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else os.cpu_count()
-        ncores = min(ncores, int(os.environ.get("OMP_NUM_THREADS", ncores)))
-        res = {}
-        for nt in (ncores, 1):
-            h_sg = [np.zeros((r, H), np.float32 if args.accumulate else ndt) for r in prob.src_rows()]
-            oracle.set_threads(nt)
-            t0 = time.perf_counter()
-            prob.forward(h_src, h_dst)
-            t1 = time.perf_counter()
-            if args.accumulate:
-                prob.backward_accumulate(h_grad, h_sg)
-            elif args.dtype == "f32":
-                prob.backward_f32(h_grad, h_sg)
-            else:
-                prob.backward_bf16(h_grad, h_sg)
-            t2 = time.perf_counter()
-            res[nt] = (t1 - t0, t2 - t1)
-            log(f"[bench] oracle {nt} thread(s): fwd {t1 - t0:.3f} s, bwd {t2 - t1:.3f} s")
-        p0 = s["plan"].info
-        ob = (1 + p0.dst_copies) * m.n_rows * p0.row_bytes + (
-            p0.dst_copies * m.n_rows * p0.row_bytes + p0.src_copies * 2 * m.n_rows * H * 4 if args.accumulate
-            else (p0.dst_copies + p0.src_copies) * m.n_rows * p0.row_bytes)
-        cpu_baseline = {
-            "value": ob / sum(res[ncores]) / 1e9, "unit": "GB/s", "cores": ncores, "kind": "oracle",
-            "sample": f"one full forward+backward pass of {w.name} (microbatch 0), {ob / 1e9:.2f} GB algorithmic",
-            "fwd_s": res[ncores][0], "bwd_s": res[ncores][1],
-            "one_thread_value": ob / sum(res[1]) / 1e9, "one_thread_fwd_s": res[1][0], "one_thread_bwd_s": res[1][1],
-        }
-        # The GPU results of the last step must equal what the oracle just computed: the source
-        # gradients everywhere, the destination buffers on every image-token row (the oracle's
-        # forward has just rewritten those rows of the GPU's own output; text rows are whatever
-        # the random prefill was).
-        if args.accumulate:                                    # binary32 accumulators whatever the gradients' dtype
-            ok_b = all(np.array_equal(t.cpu().numpy().view(np.uint32), h.view(np.uint32))
-                       for t, h in zip(s["sgrad"][:n_s], h_sg))
-        else:
-            ok_b = all(same(host(t), h) for t, h in zip(s["sgrad"][:n_s], h_sg))
-        ok_f = all(same(host(t), h) for t, h in zip(s["dst"][:n_d], h_dst))
-        cpu_baseline["gpu_matches_oracle"] = bool(ok_b and ok_f)
-        cpu_baseline["gpu_matches_oracle_forward"] = bool(ok_f)
-        cpu_baseline["gpu_matches_oracle_backward"] = bool(ok_b)
+    # ---- every other workload and variant, fewer steps, oracle check on all cores ----
+    configs = None
+    if not single:
+        configs = [compact("long_context", r)]
+        for label, workload, flags in EXTRA_CASES:
+            rc = run_case(dict(workload=workload, **flags), max(3, min(args.steps, 10)), max(1, min(args.warmup, 3)),
+                          "none" if args.no_cpu_baseline else "check", tag=label)
+            rc.pop("_dims")
+            configs.append(compact(label, rc))
 
     out = {
         "metric": "boundary fwd+bwd effective HBM GB/s and % of MI355X HBM peak, 1 GPU",
-        "value": value, "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
-        "ms_per_step": ms_per_step, "higher_is_better": True, "scaling": "weak",
+        "value": r["value"], "unit": "GB/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": r["ms_per_step"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": args.dtype, "data": "synthetic",
-        "config": {"workload": w.name, "src": f"tp{w.src.tp}dp{w.src.dp}",
-                   "dst": f"tp{w.dst.tp}cp{w.dst.cp}dp{w.dst.dp}",
-                   "batch": maps[0].batch, "seq": maps[0].seq, "hidden": H, "microbatches": len(maps),
-                   "tp_mode": "seq_shard" if args.seq_shard else "replicate", "row_order": args.row_order,
-                   "backward": "accumulate_f32" if args.accumulate else "overwrite",
-                   "accumulate_dtype": "f32", "launches_per_direction": n_launch, "launch_shapes": shapes, "tuned": args.tune,
-                   "submission": "hip_graph_replay" if args.graph else "eager",
-                   "image_rows": int(sum(m.n_rows for m in maps)), "boundary_bytes": boundary,
-                   },
-        "pct_of_hbm_peak": 100.0 * value / HBM_PEAK_GBPS,
-        "forward": {"bytes": fwd_bytes, "median_ms": f_med, "min_ms": min(fwd_ms), "max_ms": max(fwd_ms),
-                    "GBps": fwd_bytes / f_med / 1e6, "pct_of_hbm_peak": fwd_bytes / f_med / 1e6 / HBM_PEAK_GBPS * 100},
-        "backward": {"bytes": bwd_bytes, "median_ms": b_med, "min_ms": min(bwd_ms), "max_ms": max(bwd_ms),
-                     "GBps": bwd_bytes / b_med / 1e6, "pct_of_hbm_peak": bwd_bytes / b_med / 1e6 / HBM_PEAK_GBPS * 100},
-        "ms_per_step_with_kernel_events": total_events_s * 1e3 / args.steps,
-        "host_submit_ms_per_step": enqueue_s * 1e3 / args.steps,
-        "ms_per_step_to_stream_sync": stream_sync_s * 1e3 / args.steps,
-        "untimed_rehearsal_steps": rehearsal,
-        "plan_build_ms": plan_ms, "plan_rebuild_ms": plan_rebuild_ms, "plan_tune_ms": tune_ms,
-        "device_copy_GBps": copy_gbps,
-        "pattern_ceiling": {"forward_GBps": ceil_f, "backward_GBps": ceil_b, "array_bytes": arr,
-                            "forward_shape": shape_f, "backward_shape": shape_b},
-        "roofline": roofline,
-        "cpu_baseline": cpu_baseline,
     }
+    out.update({k: v for k, v in r.items() if k not in out})
+    out["device_copy_GBps"] = copy_gbps
+    out["pattern_ceiling"] = {"forward_GBps": ceil_f, "backward_GBps": ceil_b, "array_bytes": arr,
+                              "forward_shape": shape_f, "backward_shape": shape_b}
+    out["kernel_sources_sha256"] = kernel_source_digest()
+    if configs is not None:
+        out["configs"] = configs
+        out["all_configs_match_oracle"] = None if args.no_cpu_baseline else all(c["gpu_matches_oracle"] for c in configs)
+        out["min_frac_over_configs"] = min(min(c["fwd_frac"], c["bwd_frac"]) for c in configs if c["workload"] != "tiny")
     print(json.dumps(out), flush=True)
     return 0
 

@@ -366,6 +366,27 @@ int64_t hp_get_option(const char *key);     /* INT64_MIN for an unknown key */
 int hp_probe_stream(int32_t n_read, int32_t n_write, int64_t bytes_per_array,
                     const hp_launch_t *shape, double *gbps_out, hp_launch_t *best_shape);
 
+/* The same probe with a fixed launch shape (required) and another way of
+ * handing tiles to workgroups, to show what the transform kernels' schedule
+ * (HP_PROBE_ONESHOT) gains or loses against the alternatives on this machine:
+ *   HP_PROBE_XCD_CHUNKED     one-shot workgroups, but the tile order is remapped
+ *                            so that the workgroups landing on one of the 8 XCDs
+ *                            (round-robin by workgroup id) walk one contiguous
+ *                            eighth of every array;
+ *   HP_PROBE_PERSISTENT      a grid of waves_per_cu / (block_threads / 64)
+ *                            workgroups per compute unit (8 per unit when
+ *                            waves_per_cu is 0); each workgroup loops over the
+ *                            tiles with the grid size as stride;
+ *   HP_PROBE_PERSISTENT_XCD  persistent, each XCD's workgroups stride through
+ *                            their own contiguous eighth.
+ * Otherwise as hp_probe_stream (allocates its own buffers, SYNCHRONOUS). */
+#define HP_PROBE_ONESHOT        0
+#define HP_PROBE_XCD_CHUNKED    1
+#define HP_PROBE_PERSISTENT     2
+#define HP_PROBE_PERSISTENT_XCD 3
+int hp_probe_stream_ex(int32_t n_read, int32_t n_write, int64_t bytes_per_array,
+                       const hp_launch_t *shape, int32_t schedule, double *gbps_out);
+
 /* Kernel timing for measurement harnesses.  hp_profile_enable(n) with n > 0
  * creates n HIP event pairs; from then on each hp_forward / hp_backward launch
  * (in call order, any thread) is stamped with the begin and end time of its own

@@ -70,7 +70,7 @@ EXPORTS = ["hp_plan_create", "hp_plan_create_host", "hp_plan_create_batched", "h
            "hp_release_cached_memory", "hp_forget_tuned_shapes",
            "hp_plan_query", "hp_plan_src_rows", "hp_plan_segments", "hp_plan_get_launch",
            "hp_plan_set_launch", "hp_plan_tune", "hp_plan_tune_accumulate", "hp_forward", "hp_backward", "hp_backward_accumulate",
-           "hp_set_option", "hp_get_option", "hp_probe_stream", "hp_profile_enable", "hp_profile_read",
+           "hp_set_option", "hp_get_option", "hp_probe_stream", "hp_probe_stream_ex", "hp_profile_enable", "hp_profile_read",
            "hp_strerror", "hp_last_hip_error", "hp_version"]
 
 _handle = None
@@ -117,6 +117,8 @@ def _lib():
     L.hp_probe_stream.argtypes = [i32, i32, i64, C.POINTER(hp_launch_t), C.POINTER(C.c_double),
                                   C.POINTER(hp_launch_t)]
     L.hp_probe_stream.restype = C.c_int
+    L.hp_probe_stream_ex.argtypes = [i32, i32, i64, C.POINTER(hp_launch_t), i32, C.POINTER(C.c_double)]
+    L.hp_probe_stream_ex.restype = C.c_int
     L.hp_profile_enable.argtypes = [i32]
     L.hp_profile_read.argtypes = [C.POINTER(C.c_float), C.POINTER(i32), i32]
     L.hp_strerror.argtypes = [C.c_int]
@@ -169,6 +171,19 @@ def hp_probe_stream(n_read: int, n_write: int, bytes_per_array: int, shape: Opti
     _check(_lib().hp_probe_stream(n_read, n_write, int(bytes_per_array), arg, C.byref(out), C.byref(best)),
            "hp_probe_stream")
     return out.value, {f[0]: getattr(best, f[0]) for f in best._fields_}
+
+
+PROBE_SCHEDULES = {"oneshot": 0, "xcd_chunked": 1, "persistent": 2, "persistent_xcd": 3}
+
+
+def hp_probe_stream_ex(n_read: int, n_write: int, bytes_per_array: int, shape: dict, schedule) -> float:
+    """GB/s of the streaming probe in the given launch shape with tiles handed
+    to workgroups by `schedule` (a name in PROBE_SCHEDULES or its number)."""
+    out = C.c_double(0.0)
+    sched = PROBE_SCHEDULES[schedule] if isinstance(schedule, str) else int(schedule)
+    _check(_lib().hp_probe_stream_ex(n_read, n_write, int(bytes_per_array), C.byref(hp_launch_t(**shape)), sched,
+                                     C.byref(out)), "hp_probe_stream_ex")
+    return out.value
 
 
 def hp_profile_enable(max_launches: int) -> None:

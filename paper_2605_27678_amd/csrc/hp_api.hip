@@ -302,7 +302,13 @@ struct ProbeArgs {
     uint32_t n_read, n_write;
     uint64_t n_chunks;       // 16-byte chunks per array
     uint32_t chunks_per_wg;
+    uint32_t n_tiles;        // ceil(n_chunks / chunks_per_wg)
+    uint32_t tiles_per_xcd;  // ceil(n_tiles / kXcds), for the XCD-chunked schedules
 };
+
+// Workgroups are handed to the chip's 8 accelerator dies (XCDs, each with its
+// own L2) round-robin by workgroup id.
+constexpr uint32_t kXcds = 8;
 
 template <int U, bool GUARD, bool NTL, bool NTS>
 __device__ __forceinline__ void probe_group(const ProbeArgs &a, uint64_t base, uint32_t done, uint32_t n) {
@@ -336,8 +342,8 @@ __device__ __forceinline__ void probe_group(const ProbeArgs &a, uint64_t base, u
 }
 
 template <bool NTL, bool NTS>
-__global__ void __launch_bounds__(1024) hp_probe_kernel(const ProbeArgs a) {
-    const uint64_t base = (uint64_t)blockIdx.x * a.chunks_per_wg;
+__device__ __forceinline__ void probe_tile(const ProbeArgs &a, uint32_t tile) {
+    const uint64_t base = (uint64_t)tile * a.chunks_per_wg;
     const uint64_t left = a.n_chunks - base;
     const uint32_t n = left < a.chunks_per_wg ? (uint32_t)left : a.chunks_per_wg;
     const uint32_t step = blockDim.x;
@@ -345,6 +351,30 @@ __global__ void __launch_bounds__(1024) hp_probe_kernel(const ProbeArgs a) {
     for (; n - done >= 2 * step; done += 2 * step) probe_group<2, false, NTL, NTS>(a, base, done, n);
     if (n - done >= step) { probe_group<1, false, NTL, NTS>(a, base, done, n); done += step; }
     if (n - done > 0) probe_group<1, true, NTL, NTS>(a, base, done, n);
+}
+
+// SCHED = how tiles are handed to workgroups (HP_PROBE_* in hp.h):
+//   one-shot       one short-lived workgroup per tile, tile = workgroup id (what the transform kernels do)
+//   XCD-chunked    one-shot, but the workgroups that land on one XCD walk one contiguous eighth of the tiles
+//   persistent     a grid of a few workgroups per CU; each loops over the tiles with the grid as stride
+//   persistent+XCD persistent, each XCD's workgroups stride through their own contiguous eighth
+// Every loop is bounded by n_tiles and every workgroup leaves it.
+template <bool NTL, bool NTS, int SCHED>
+__global__ void __launch_bounds__(1024) hp_probe_kernel(const ProbeArgs a) {
+    if constexpr (SCHED == HP_PROBE_ONESHOT) {
+        probe_tile<NTL, NTS>(a, blockIdx.x);
+    } else if constexpr (SCHED == HP_PROBE_XCD_CHUNKED) {
+        const uint32_t tile = (blockIdx.x % kXcds) * a.tiles_per_xcd + blockIdx.x / kXcds;
+        if (blockIdx.x / kXcds < a.tiles_per_xcd && tile < a.n_tiles) probe_tile<NTL, NTS>(a, tile);
+    } else if constexpr (SCHED == HP_PROBE_PERSISTENT) {
+        for (uint32_t tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) probe_tile<NTL, NTS>(a, tile);
+    } else {
+        const uint32_t xcd = blockIdx.x % kXcds, stride = gridDim.x / kXcds;     // grid is a multiple of kXcds
+        for (uint32_t t = blockIdx.x / kXcds; t < a.tiles_per_xcd; t += stride) {
+            const uint32_t tile = xcd * a.tiles_per_xcd + t;
+            if (tile < a.n_tiles) probe_tile<NTL, NTS>(a, tile);
+        }
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -470,9 +500,19 @@ enum Direction { kForward = 0, kBackward = 1, kBackwardAcc = 2 };
 
 // Enqueues one kernel for direction `dir` with launch shape `L`.  `lane` is the
 // lane chunk chosen by prepare(): bytes for forward, elements for backward.
+int enqueue_params(const hp_plan *p, Direction dir, const hp::Launch &L, const BufTable &bt, int lane,
+                   hipStream_t stream, EventPair ev, const KParams &k);
+
 int enqueue(const hp_plan *p, Direction dir, const hp::Launch &L, const BufTable &bt, int lane,
             hipStream_t stream, EventPair ev) {
-    const KParams k = hp::kernel_params(*p, L.tile_variant, p->d_segs, p->d_tree);
+    const int rc = enqueue_params(p, dir, L, bt, lane, stream, ev,
+                                  hp::kernel_params(*p, L.tile_variant, p->d_segs, p->d_tree));
+    if (rc == HP_OK) p->note_stream((void *)stream);
+    return rc;
+}
+
+int enqueue_params(const hp_plan *p, Direction dir, const hp::Launch &L, const BufTable &bt, int lane,
+                   hipStream_t stream, EventPair ev, const KParams &k) {
     LaunchCfg c;
     c.grid = dim3(p->n_tiles(L.tile_variant));
     c.block = dim3((unsigned)L.block);
@@ -497,7 +537,6 @@ int enqueue(const hp_plan *p, Direction dir, const hp::Launch &L, const BufTable
         }
     }
     if (hip_failed(hipGetLastError())) return HP_EHIP;
-    p->note_stream((void *)stream);
     return HP_OK;
 }
 
@@ -509,13 +548,15 @@ int enqueue(const hp_plan *p, Direction dir, const hp::Launch &L, const BufTable
 // for backward (the binary32 accumulators of kBackwardAcc are addressed in
 // 16-byte or 4-byte chunks).
 int prepare(const hp_plan *p, Direction dir, const void *const *src, const void *const *dst,
-            BufTable *bt, int *lane) {
+            BufTable *bt, int *lane, bool plan_tables = true) {
     if (!p || !src || !dst) return HP_EINVAL;
     if (p->segments.empty()) return HP_OK;
-    if (!p->d_segs) return HP_ESTATE;
-    int dev = -1;
-    if (hip_failed(hipGetDevice(&dev))) return HP_EHIP;
-    if (dev != p->device) return HP_ESTATE;
+    if (plan_tables) {                                      // the launch will read the plan's own device tables
+        if (!p->d_segs) return HP_ESTATE;
+        int dev = -1;
+        if (hip_failed(hipGetDevice(&dev))) return HP_EHIP;
+        if (dev != p->device) return HP_ESTATE;
+    }
     std::memset(bt, 0, sizeof(*bt));
     int n = 0;
     uint64_t src_bits = 0, dst_bits = (uint64_t)p->row_bytes;
@@ -879,34 +920,57 @@ int tune_direction(hp_plan *p, Direction dir, const BufTable &bt, int lane, hipS
     return rc;
 }
 
-void launch_probe(const ProbeArgs &args, const LaunchCfg &c, int nontemporal) {
+template <int SCHED>
+void launch_probe_sched(const ProbeArgs &args, const LaunchCfg &c, int nontemporal) {
     switch (nontemporal & 3) {
-        case 0: HP_LAUNCH((hp_probe_kernel<false, false>), c, args); break;
-        case 1: HP_LAUNCH((hp_probe_kernel<true, false>), c, args); break;
-        case 2: HP_LAUNCH((hp_probe_kernel<false, true>), c, args); break;
-        default: HP_LAUNCH((hp_probe_kernel<true, true>), c, args); break;
+        case 0: HP_LAUNCH((hp_probe_kernel<false, false, SCHED>), c, args); break;
+        case 1: HP_LAUNCH((hp_probe_kernel<true, false, SCHED>), c, args); break;
+        case 2: HP_LAUNCH((hp_probe_kernel<false, true, SCHED>), c, args); break;
+        default: HP_LAUNCH((hp_probe_kernel<true, true, SCHED>), c, args); break;
+    }
+}
+
+void launch_probe(const ProbeArgs &args, const LaunchCfg &c, int nontemporal, int schedule) {
+    switch (schedule) {
+        case HP_PROBE_ONESHOT: launch_probe_sched<HP_PROBE_ONESHOT>(args, c, nontemporal); break;
+        case HP_PROBE_XCD_CHUNKED: launch_probe_sched<HP_PROBE_XCD_CHUNKED>(args, c, nontemporal); break;
+        case HP_PROBE_PERSISTENT: launch_probe_sched<HP_PROBE_PERSISTENT>(args, c, nontemporal); break;
+        default: launch_probe_sched<HP_PROBE_PERSISTENT_XCD>(args, c, nontemporal); break;
     }
 }
 
 // Same steady-state burst timing as time_candidate, for the probe kernel.
+// `n_cus` is only used by the persistent schedules: their grid is the number of
+// workgroups the resident-wave cap allows per compute unit times the compute
+// units (8 workgroups per unit when there is no cap), rounded to whole XCDs.
 float time_probe(const ProbeArgs &a, const hp::Launch &L, hipStream_t stream, const BurstEvents &ev,
-                 int bursts, int burst) {
+                 int bursts, int burst, int schedule = HP_PROBE_ONESHOT, int n_cus = 256) {
     ProbeArgs args = a;
     args.chunks_per_wg = hp::tile_bytes_of(L.tile_variant) / 16u;
+    args.n_tiles = (uint32_t)((a.n_chunks + args.chunks_per_wg - 1) / args.chunks_per_wg);
+    args.tiles_per_xcd = (args.n_tiles + kXcds - 1) / kXcds;
     LaunchCfg c;
-    c.grid = dim3((unsigned)((a.n_chunks + args.chunks_per_wg - 1) / args.chunks_per_wg));
+    if (schedule == HP_PROBE_ONESHOT) c.grid = dim3(args.n_tiles);
+    else if (schedule == HP_PROBE_XCD_CHUNKED) c.grid = dim3(args.tiles_per_xcd * kXcds);
+    else {
+        const int per_wg = L.block / 64;
+        const int wgs_per_cu = L.waves_per_cu > 0 ? std::max(1, L.waves_per_cu / per_wg) : std::max(1, 8 / per_wg);
+        uint32_t g = (uint32_t)(wgs_per_cu * n_cus) / kXcds * kXcds;
+        g = std::max(kXcds, std::min(g, (args.n_tiles + kXcds - 1) / kXcds * kXcds));
+        c.grid = dim3(g);
+    }
     c.block = dim3((unsigned)L.block);
     c.lds_bytes = lds_for_cap(L.block, L.waves_per_cu);
     c.stream = stream;
     float t[8];
     if (bursts > 8) bursts = 8;
-    launch_probe(args, c, L.nontemporal);                                 // warm-up
+    launch_probe(args, c, L.nontemporal, schedule);                       // warm-up
     for (int b = 0; b < bursts; ++b) {
         for (int i = 0; i < burst; ++i) {
             c.ev = EventPair{};
             if (i == 0) c.ev = EventPair{ev.e[0], ev.e[1]};
             else if (i == burst - 1) c.ev = EventPair{ev.e[2], ev.e[3]};
-            launch_probe(args, c, L.nontemporal);
+            launch_probe(args, c, L.nontemporal, schedule);
         }
         if (hip_failed(hipGetLastError()) || hip_failed(hipEventSynchronize(ev.e[3]))) return -1.f;
         float ms = 0.f;
@@ -1070,9 +1134,14 @@ int hp_plan_tune(hp_plan_t *p, const void *const *src_bufs, void *const *dst_buf
     return rc;
 }
 
-int hp_probe_stream(int32_t n_read, int32_t n_write, int64_t bytes_per_array, const hp_launch_t *shape,
-                    double *gbps_out, hp_launch_t *best_shape) {
+}  // extern "C"
+
+namespace {
+int probe_stream(int32_t n_read, int32_t n_write, int64_t bytes_per_array, const hp_launch_t *shape,
+                 int schedule, double *gbps_out, hp_launch_t *best_shape) {
     if (n_read < 0 || n_read > 8 || n_write < 1 || n_write > 8 || !gbps_out) return HP_EINVAL;
+    if (schedule < HP_PROBE_ONESHOT || schedule > HP_PROBE_PERSISTENT_XCD) return HP_EINVAL;
+    if (bytes_per_array > 0 && bytes_per_array / 1024 > 0x7fffffff) return HP_EINVAL;   // tile count in 32 bits
     if (bytes_per_array < 65536 || bytes_per_array % 16 || bytes_per_array > ((int64_t)1 << 36)) return HP_EINVAL;
     hp::Launch fixed{};
     if (shape) {
@@ -1098,11 +1167,18 @@ int hp_probe_stream(int32_t n_read, int32_t n_write, int64_t bytes_per_array, co
     for (int i = 0; i < n_read; ++i) a.rd[i] = (const u32x4 *)mem[i];
     for (int i = 0; i < n_write; ++i) a.wr[i] = (u32x4 *)mem[n_read + i];
     if (rc == HP_OK && (!ev.create() || hip_failed(hipStreamCreate(&stream)))) rc = HP_EHIP;
+    int n_cus = 256;
+    if (rc == HP_OK) {
+        int dev = 0;
+        hipDeviceProp_t prop;
+        if (hip_failed(hipGetDevice(&dev)) || hip_failed(hipGetDeviceProperties(&prop, dev))) rc = HP_EHIP;
+        else if (prop.multiProcessorCount > 0) n_cus = prop.multiProcessorCount;
+    }
     float best_ms = 1e30f;
     hp::Launch best = fixed;
     if (rc == HP_OK) {
         if (shape) {
-            best_ms = time_probe(a, fixed, stream, ev, 3, 4);
+            best_ms = time_probe(a, fixed, stream, ev, 3, 4, schedule, n_cus);
             if (best_ms < 0) rc = HP_EHIP;
         } else {
             const int blocks[] = {64, 128, 256};
@@ -1139,6 +1215,20 @@ int hp_probe_stream(int32_t n_read, int32_t n_write, int64_t bytes_per_array, co
         best_shape->nontemporal = best.nontemporal;
     }
     return HP_OK;
+}
+}  // namespace
+
+extern "C" {
+
+int hp_probe_stream(int32_t n_read, int32_t n_write, int64_t bytes_per_array, const hp_launch_t *shape,
+                    double *gbps_out, hp_launch_t *best_shape) {
+    return probe_stream(n_read, n_write, bytes_per_array, shape, HP_PROBE_ONESHOT, gbps_out, best_shape);
+}
+
+int hp_probe_stream_ex(int32_t n_read, int32_t n_write, int64_t bytes_per_array, const hp_launch_t *shape,
+                       int32_t schedule, double *gbps_out) {
+    if (!shape) return HP_EINVAL;
+    return probe_stream(n_read, n_write, bytes_per_array, shape, schedule, gbps_out, nullptr);
 }
 
 int hp_plan_tune_accumulate(hp_plan_t *p, const void *const *dst_grad_bufs, void *const *src_accum_bufs,

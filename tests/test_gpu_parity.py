@@ -11,7 +11,7 @@ import torch
 import paper_2605_27678_amd as hp
 from oracle import oracle
 from paper_2605_27678_amd import workloads as wl
-from parity import _to_host_bits, check_case, make_inputs
+from parity import _to_host_bits, check_case, check_case_extended, make_inputs
 
 pytestmark = pytest.mark.gpu
 
@@ -312,6 +312,22 @@ def test_full_large_scale():
     w = wl.large_scale()
     info = check_case(w.src, w.dst, w.maps[0], seed=5, gen_device="cuda")
     assert (info.src_copies, info.dst_copies) == (2, 8)
+
+
+@pytest.mark.parametrize("name,hidden", [("non_colocated", 256), ("large_scale", 256), ("long_context", 320)])
+def test_contiguous_cp_split_on_the_named_grids(name, hidden):
+    """The paper gives no CP split rule; the load-balanced one is primary and the
+    contiguous one is checked on the same grids and token maps (config 4:
+    microbatches 0, 7 and 15 and the batched plan; configs 5 and 3: the whole
+    map), at a reduced hidden size."""
+    w = wl.scaled(wl.CONFIGS[name](), hidden)
+    dst = replace(w.dst, cp_split=wl.CP_CONTIGUOUS)
+    for i in ([0, 7, 15] if len(w.maps) > 1 else [0]):
+        info = check_case(w.src, dst, w.maps[i], seed=60 + i, gen_device="cuda")
+        assert info.n_rows == w.maps[i].n_rows
+    if len(w.maps) > 1:
+        _batched_case(replace(w, dst=dst), hidden, seed=6)
+    check_case_extended(w.src, dst, w.maps[0], seed=61)
 
 
 # ---- batched plans and the tuner ------------------------------------------------
