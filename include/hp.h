@@ -287,6 +287,31 @@ int hp_backward(const hp_plan_t *plan, const void *const *dst_grad_bufs,
 int hp_backward_accumulate(const hp_plan_t *plan, const void *const *dst_grad_bufs,
                            void *const *src_accum_bufs, void *stream);
 
+/* hp_forward_static - hp_forward for callers that cannot allocate device memory
+ * or let the library do so: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid hipMalloc.  hp_forward reads its plan's tables from a
+ * device block that hp_plan_create allocated; this call instead takes ANY plan
+ * (normally a host-only one from hp_plan_create_host or the host_only variants,
+ * whose creation makes no HIP call), writes the tables this launch needs - the
+ * segment descriptors and the search tree of the plan's forward tile size -
+ * into a fixed array that the library holds in each GPU's memory from load to
+ * process end (HP_STATIC_MAX_TABLE_BYTES, 64 KiB: about 1700 segments), and
+ * launches the same kernel on them.  The table bytes travel as arguments of
+ * small copy kernels on `stream` ahead of the transform kernel, so no host
+ * buffer has to outlive the call.  It calls no hipMalloc / hipFree / hipMemcpy
+ * and no other allocating routine.
+ *   plan, src_bufs, dst_bufs, stream: as for hp_forward; the result is the same.
+ * Returns HP_ELAYOUT when the tables exceed HP_STATIC_MAX_TABLE_BYTES (use
+ * hp_forward with a device plan then), otherwise hp_forward's codes; HP_ESTATE
+ * is not returned for host-only plans here.
+ * All calls on one GPU share that GPU's array and it keeps the last call's
+ * tables: calls on the SAME stream are ordered by the stream, calls that overlap
+ * on different streams (or threads using different streams) of one GPU race on
+ * it and must be serialised by the caller.  No timing events are attached. */
+#define HP_STATIC_MAX_TABLE_BYTES 65536
+int hp_forward_static(const hp_plan_t *plan, const void *const *src_bufs,
+                      void *const *dst_bufs, void *stream);
+
 /* Launch shape of one direction of a plan (direction 0 = hp_forward,
  * 1 = hp_backward, 2 = hp_backward_accumulate).  A plan starts from the
  * process-wide defaults below (the accumulating backward from the backward

@@ -378,6 +378,25 @@ __global__ void __launch_bounds__(1024) hp_probe_kernel(const ProbeArgs a) {
 }
 
 // ---------------------------------------------------------------------------
+// hp_forward_static: the plan tables of one launch in a file-scope device array
+// ---------------------------------------------------------------------------
+// One array per GPU, held until the process ends.  In host code the name below is
+// only a handle for hipGetSymbolAddress; every use of the memory goes through
+// the per-device pointer that call returns (static_tables()).
+static __device__ __align__(256) unsigned char scratch[HP_STATIC_MAX_TABLE_BYTES];
+
+// Table bytes travel in the kernel-argument segment (which a HIP graph node
+// keeps by value), a chunk per launch: no host buffer has to outlive the call
+// and nothing is allocated or copied by the runtime.
+constexpr uint32_t kChunkWords = 896;                       // 3584 bytes, under the 4 KiB argument limit
+struct TableChunk { uint32_t w[kChunkWords]; };
+
+__global__ void __launch_bounds__(256)
+hp_table_upload_kernel(const TableChunk c, uint32_t *dst, uint32_t n_words) {
+    for (uint32_t i = threadIdx.x; i < n_words && i < kChunkWords; i += blockDim.x) dst[i] = c.w[i];
+}
+
+// ---------------------------------------------------------------------------
 // host side
 // ---------------------------------------------------------------------------
 
@@ -981,6 +1000,37 @@ float time_probe(const ProbeArgs &a, const hp::Launch &L, hipStream_t stream, co
     return t[bursts / 2];
 }
 
+// Device address of this GPU's `scratch` array, looked up once per device with
+// that device current (each GPU holds its own copy at its own address).
+unsigned char *static_tables(int *rc) {
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static unsigned char *ptr[kMaxDevices] = {nullptr};
+    int dev = -1;
+    if (hip_failed(hipGetDevice(&dev))) { *rc = HP_EHIP; return nullptr; }
+    if (dev < 0 || dev >= kMaxDevices) { *rc = HP_ESTATE; return nullptr; }
+    std::lock_guard<std::mutex> lk(mu);
+    if (!ptr[dev]) {
+        void *a = nullptr;
+        if (hip_failed(hipGetSymbolAddress(&a, HIP_SYMBOL(scratch))) || !a) { *rc = HP_EHIP; return nullptr; }
+        ptr[dev] = (unsigned char *)a;
+    }
+    return ptr[dev];
+}
+
+// Copies n_words 32-bit words from host memory into device memory at `dst` with
+// small kernels that carry the words in their arguments.
+int upload_words(unsigned char *dst, const uint32_t *src, size_t n_words, hipStream_t stream) {
+    for (size_t done = 0; done < n_words; done += kChunkWords) {
+        const uint32_t n = (uint32_t)std::min<size_t>(kChunkWords, n_words - done);
+        TableChunk c;
+        std::memcpy(c.w, src + done, (size_t)n * 4);
+        hipLaunchKernelGGL(hp_table_upload_kernel, dim3(1), dim3(256), 0, stream, c, (uint32_t *)dst + done, n);
+        if (hip_failed(hipGetLastError())) return HP_EHIP;
+    }
+    return HP_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -1096,6 +1146,31 @@ int hp_backward_accumulate(const hp_plan_t *p, const void *const *dst_grad_bufs,
     int rc = prepare(p, kBackwardAcc, (const void *const *)src_accum_bufs, dst_grad_bufs, &bt, &lane);
     if (rc != HP_OK || p->segments.empty()) return rc;
     return enqueue(p, kBackwardAcc, p->acc, bt, lane, (hipStream_t)stream, next_event_pair(2));
+}
+
+int hp_forward_static(const hp_plan_t *p, const void *const *src_bufs, void *const *dst_bufs, void *stream) {
+    BufTable bt;
+    int width = 0;
+    int rc = prepare(p, kForward, src_bufs, (const void *const *)dst_bufs, &bt, &width, /*plan_tables=*/false);
+    if (rc != HP_OK || p->segments.empty()) return rc;
+    // what this launch reads: the segment descriptors and the search tree of its tile size only
+    const hp::Launch &L = p->fwd;
+    const hp::TreeInfo &ti = p->tree_info[L.tile_variant];
+    const size_t seg_bytes = (p->dsegs.size() * sizeof(hp::Seg) + 63) / 64 * 64;          // tree nodes stay 64-byte aligned
+    const uint32_t tree_begin = ti.level_off[0];
+    const uint32_t tree_end = L.tile_variant + 1 < hp::kTileVariants ? p->tree_info[L.tile_variant + 1].level_off[0]
+                                                                      : (uint32_t)p->tree.size();
+    const size_t tree_bytes = (size_t)(tree_end - tree_begin) * sizeof(uint32_t);
+    if (seg_bytes + tree_bytes > (size_t)HP_STATIC_MAX_TABLE_BYTES) return HP_ELAYOUT;
+    unsigned char *tables = static_tables(&rc);
+    if (!tables) return rc;
+    hipStream_t st = (hipStream_t)stream;
+    rc = upload_words(tables, (const uint32_t *)p->dsegs.data(), p->dsegs.size() * sizeof(hp::Seg) / 4, st);
+    if (rc == HP_OK) rc = upload_words(tables + seg_bytes, p->tree.data() + tree_begin, tree_end - tree_begin, st);
+    if (rc != HP_OK) return rc;
+    KParams k = hp::kernel_params(*p, L.tile_variant, (const hp::Seg *)tables, (const uint32_t *)(tables + seg_bytes));
+    for (uint32_t l = 0; l < k.n_levels; ++l) k.level_off[l] -= tree_begin;               // offsets inside the copied tree
+    return enqueue_params(p, kForward, L, bt, width, st, EventPair{}, k);
 }
 
 int hp_plan_tune(hp_plan_t *p, const void *const *src_bufs, void *const *dst_bufs,
