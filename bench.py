@@ -26,6 +26,7 @@ import argparse
 import hashlib
 import json
 import os
+import re
 import statistics
 import subprocess
 import sys
@@ -35,6 +36,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBPS = 8000.0          # MI355X published HBM3E bandwidth
+PROFILES = os.path.join(ROOT, "profiles")
 KERNEL_SOURCES = ("hp_api.hip", "hp_tile.hpp", "hp_plan.cpp", "hp_plan.hpp")
 WORKLOADS = ["tiny", "colocated4", "colocated4_dense", "long_context", "non_colocated", "large_scale"]
 
@@ -84,7 +86,7 @@ def traffic_label(case: dict) -> str:
 def read_traffic(label: str):
     """HBM bytes per launch measured with rocprofv3 counters, if a summary for
     this case has been committed under profiles/ (key = value lines)."""
-    path = os.path.join(ROOT, "profiles", f"hbm_traffic_{label}.txt")
+    path = os.path.join(PROFILES, f"hbm_traffic_{label}.txt")
     out = {}
     if os.path.exists(path):
         for line in open(path):
@@ -95,7 +97,7 @@ def read_traffic(label: str):
                     out[k.strip()] = float(v)
                 except ValueError:
                     out[k.strip()] = v
-        out["_file"] = os.path.relpath(path, ROOT)
+        out["_file"] = os.path.join("profiles", os.path.basename(path))
     return out
 
 
@@ -553,8 +555,16 @@ def summarize_traffic(args) -> int:
         fb = info.fwd_bytes
         bb = info.bwd_accum_bytes if acc else info.bwd_bytes
         res = {}
-        for d, name, g in ((0, "hp_forward_kernel", grid[0]), (1, "hp_backward_kernel", grid[2 if acc else 1])):
-            pred = lambda x, name=name, g=g: name in x[0] and x[1] == g
+        # the kernels are template instances: forward <lane type, NREP, ...>, backward <dtype, elements,
+        # accumulate, NREP, ...>, NREP = destination copies when that is 1, 2, 4 or 8 and 0 otherwise
+        nrep = info.dst_copies if info.dst_copies in (1, 2, 4, 8) else 0
+        pats = {0: re.compile(r"hp_forward_kernel<[^,]+, %d, " % nrep),
+                1: re.compile(r"hp_backward_kernel<\d+, \d+, %s, %d, " % ("true" if acc else "false", nrep))}
+        if info.boundary_bytes < (1 << 20):
+            log(f"{label}: {info.boundary_bytes} B boundary - too small for a per-launch traffic figure, skipped")
+            continue
+        for d, g in ((0, grid[0]), (1, grid[2 if acc else 1])):
+            pred = lambda x, pat=pats[d], g=g: pat.search(x[0]) is not None and x[1] == g
             f, w_ = mean_of(fetch, pred), mean_of(write, pred)
             if f[0] is None or w_[0] is None:
                 res = None
@@ -564,7 +574,7 @@ def summarize_traffic(args) -> int:
             log(f"{label}: no dispatches with the expected grid sizes {grid} - skipped")
             continue
         tag = traffic_label(case)
-        path = os.path.join(ROOT, "profiles", f"hbm_traffic_{tag}.txt")
+        path = os.path.join(PROFILES, f"hbm_traffic_{tag}.txt")
         (ff, fw), (bf, bw) = res[0], res[1]
         f_bytes = ff[0] * 1024 * fetch_scale + fw[0] * 1024 * write_scale
         b_bytes = bf[0] * 1024 * fetch_scale + bw[0] * 1024 * write_scale
@@ -597,7 +607,7 @@ def summarize_traffic(args) -> int:
                 f"forward_bytes_per_boundary_byte = {f_bytes / info.boundary_bytes:.4f}\n"
                 f"backward_bytes_per_boundary_byte = {b_bytes / info.boundary_bytes:.4f}\n")
         plan.close()
-        written.append(os.path.relpath(path, ROOT))
+        written.append(os.path.join("profiles", os.path.basename(path)))
         log(f"{tag}: forward x{f_bytes / fb:.4f}, backward x{b_bytes / bb:.4f} of the algorithmic bytes -> {written[-1]}")
     print(json.dumps({"written": written, "fetch_scale": fetch_scale, "write_scale": write_scale, "head": head}))
     return 0

@@ -162,10 +162,11 @@ typedef struct hp_segment {
     int64_t dst_row_stride;    /* 1 for HP_ROW_BSH, B_local for HP_ROW_SBH                    */
 } hp_segment_t;
 
-/* hp_plan_create - the paper's "derive every rank's source coordinate,
- * destination coordinate and batch interval" step (Colocated communicator,
- * second paragraph; both sides build the same static routing pattern,
- * Non-colocated communicator): validates the two grids and the token map,
+/* hp_plan_create - the construction step of a communicator: from the two grids
+ * alone every rank's place on the source side, its place on the destination
+ * side and the batch interval it exchanges are worked out once and kept
+ * (Colocated communicator, second paragraph; the non-colocated communicator
+ * builds the same fixed routing on both sides): validates the two grids and the token map,
  * builds the segment table (runs of rows contiguous on both sides) and the
  * search trees that map a workgroup to its segment on the host, and uploads
  * them to the CURRENT HIP device (a few KB; one synchronous copy into a device
@@ -221,8 +222,10 @@ int hp_plan_create_joined(const hp_layout_t *srcs, int32_t n_edges, const hp_lay
  * synchronisation: the block is not overwritten before the streams those calls
  * were enqueued on have passed them (an event per stream is recorded here and
  * waited for when the block is next handed out).  Call it with the plan's
- * device current.  A plan whose calls were recorded into a HIP graph has to
- * outlive the replays of that graph. */
+ * device current.  Every stream the plan was used on must still exist when this
+ * is called (destroy the plan before the stream, not after: the handle is
+ * queried and an event is recorded on it here).  A plan whose calls were
+ * recorded into a HIP graph has to outlive the replays of that graph. */
 void hp_plan_destroy(hp_plan_t *plan);
 
 /* hipFree()s every cached device block (at most 64 blocks of a few KB). */
@@ -239,10 +242,11 @@ int hp_plan_src_rows(const hp_plan_t *plan, int64_t *rows, int32_t cap);
  * number of segments. */
 int hp_plan_segments(const hp_plan_t *plan, hp_segment_t *out, int32_t cap);
 
-/* hp_forward - materialise the source activation in the destination layout
- * (Method: "forward materializes the activation in the destination layout";
- * fan-in concatenation in batch order, Non-colocated communicator; insertion
- * into the text embeddings, "Pipeline schedule details" phase 2).
+/* hp_forward - produce the source module's activation in the layout of the
+ * destination module (Method, paragraph on boundary edges: the forward direction
+ * of an edge; fan-in concatenation in batch order, Non-colocated communicator;
+ * insertion into the text embeddings, appendix "Pipeline schedule details",
+ * phase 2).
  *   src_bufs: HOST array of n_src_bufs DEVICE pointers, index tp + TP_src*dp,
  *             each [rows_i, hidden] of the plan's dtype.  Only copies with tp == 0 are read;
  *             entries of other copies and of empty ranks may be NULL.
@@ -250,7 +254,11 @@ int hp_plan_segments(const hp_plan_t *plan, hp_segment_t *out, int32_t cap);
  *             tp + TP_dst*(cp + CP_dst*dp), each [dst_rows_per_buf, hidden].
  *             Exactly the image-token rows are written; all other bytes (the
  *             text embeddings the caller placed there) are left as found.
- *   stream:   a hipStream_t (NULL = the default stream).
+ *   stream:   a hipStream_t (NULL = the default stream).  The call is ordered
+ *             against work on THIS stream only: whatever produced src_bufs (and
+ *             the text rows of dst_bufs) on another stream must have finished,
+ *             or the caller makes `stream` wait for it first.  The same holds
+ *             for every call below that takes a stream.
  * Pointers must be aligned to the element size; 16-byte alignment (with a row
  * size that is a multiple of 16) selects the vector path.  Returns after
  * enqueueing. */
@@ -258,9 +266,10 @@ int hp_forward(const hp_plan_t *plan, const void *const *src_bufs,
                void *const *dst_bufs, void *stream);
 
 /* hp_backward - route destination-layout gradients back to the source layout
- * (Method: "backward applies the matching reverse layout transform"; fan-in
- * backward splits along the recorded intervals; the result is placed on every
- * TP rank of the source side, Non-colocated communicator, backward paragraph).
+ * (Method, paragraph on boundary edges: the backward direction of an edge undoes
+ * the forward layout change; fan-in backward splits along the recorded
+ * intervals; the result is placed on every TP rank of the source side,
+ * Non-colocated communicator, backward paragraph).
  * The dst_copies replicas of each image-token row are summed in binary32 in
  * ascending tp order and rounded once to bf16 (HP_F32: no final rounding).
  *   dst_grad_bufs: HOST array of n_dst_bufs DEVICE pointers, same shapes as
@@ -299,7 +308,8 @@ int hp_backward_accumulate(const hp_plan_t *plan, const void *const *dst_grad_bu
  * launches the same kernel on them.  The table bytes travel as arguments of
  * small copy kernels on `stream` ahead of the transform kernel, so no host
  * buffer has to outlive the call.  It calls no hipMalloc / hipFree / hipMemcpy
- * and no other allocating routine.
+ * and no other allocating routine.  The first call on a device looks up the
+ * array's address (hipGetSymbolAddress); make that call outside graph capture.
  *   plan, src_bufs, dst_bufs, stream: as for hp_forward; the result is the same.
  * Returns HP_ELAYOUT when the tables exceed HP_STATIC_MAX_TABLE_BYTES (use
  * hp_forward with a device plan then), otherwise hp_forward's codes; HP_ESTATE
@@ -378,8 +388,9 @@ int hp_set_option(const char *key, int64_t value);
 int64_t hp_get_option(const char *key);     /* INT64_MIN for an unknown key */
 
 /* Streaming probe for measurement harnesses: the HBM rate of a plain kernel
- * that reads n_read (0..8) linear arrays and writes n_write (1..8) linear arrays
- * of bytes_per_array bytes each, with the same 16-byte lanes, one-shot
+ * that reads n_read (0..8) linear arrays and writes n_write (0..8) linear arrays
+ * (at least one array in all; n_write = 0 is a read-only stream whose data is
+ * folded and dropped) of bytes_per_array bytes each, with the same 16-byte lanes, one-shot
  * workgroups and occupancy cap as the transform kernels but no segment lookup:
  * the practical ceiling of hp_forward's 1-read : TP_dst-write pattern and of
  * hp_backward's TP_dst-read : TP_src-write pattern on this machine.  With

@@ -339,6 +339,13 @@ __device__ __forceinline__ void probe_group(const ProbeArgs &a, uint64_t base, u
         for (int u = 0; u < U; ++u)
             if (!GUARD || i[u] < n) st<u32x4, NTS>(a.wr[w] + base + i[u], acc[u]);
     }
+    if (a.n_write == 0) {
+        // read-only pattern: keep the loads alive with a store that the data never triggers
+        // (the arrays are filled with small byte patterns); wr[0] is a 16-byte sink
+#pragma unroll
+        for (int u = 0; u < U; ++u)
+            if ((acc[u].x ^ acc[u].w) == 0x9e3779b9u) a.wr[0][0] = acc[u];
+    }
 }
 
 template <bool NTL, bool NTS>
@@ -1214,7 +1221,7 @@ int hp_plan_tune(hp_plan_t *p, const void *const *src_bufs, void *const *dst_buf
 namespace {
 int probe_stream(int32_t n_read, int32_t n_write, int64_t bytes_per_array, const hp_launch_t *shape,
                  int schedule, double *gbps_out, hp_launch_t *best_shape) {
-    if (n_read < 0 || n_read > 8 || n_write < 1 || n_write > 8 || !gbps_out) return HP_EINVAL;
+    if (n_read < 0 || n_read > 8 || n_write < 0 || n_write > 8 || n_read + n_write < 1 || !gbps_out) return HP_EINVAL;
     if (schedule < HP_PROBE_ONESHOT || schedule > HP_PROBE_PERSISTENT_XCD) return HP_EINVAL;
     if (bytes_per_array > 0 && bytes_per_array / 1024 > 0x7fffffff) return HP_EINVAL;   // tile count in 32 bits
     if (bytes_per_array < 65536 || bytes_per_array % 16 || bytes_per_array > ((int64_t)1 << 36)) return HP_EINVAL;
@@ -1233,6 +1240,8 @@ int probe_stream(int32_t n_read, int32_t n_write, int64_t bytes_per_array, const
     BurstEvents ev;
     hipStream_t stream = nullptr;
     int rc = HP_OK;
+    void *sink = nullptr;                                                 // read-only pattern: where nothing is ever stored
+    if (n_write == 0 && hip_failed(hipMalloc(&sink, 256))) rc = HP_EHIP;
     for (int i = 0; i < n_read + n_write && rc == HP_OK; ++i) {
         hipError_t e = hipMalloc(&mem[i], (size_t)bytes_per_array);
         if (e == hipErrorOutOfMemory) { g_last_hip_error = (int)e; rc = HP_ENOMEM; }
@@ -1241,6 +1250,7 @@ int probe_stream(int32_t n_read, int32_t n_write, int64_t bytes_per_array, const
     }
     for (int i = 0; i < n_read; ++i) a.rd[i] = (const u32x4 *)mem[i];
     for (int i = 0; i < n_write; ++i) a.wr[i] = (u32x4 *)mem[n_read + i];
+    if (n_write == 0) a.wr[0] = (u32x4 *)sink;
     if (rc == HP_OK && (!ev.create() || hip_failed(hipStreamCreate(&stream)))) rc = HP_EHIP;
     int n_cus = 256;
     if (rc == HP_OK) {
@@ -1281,6 +1291,7 @@ int probe_stream(int32_t n_read, int32_t n_write, int64_t bytes_per_array, const
     }
     if (stream) { (void)hipStreamSynchronize(stream); (void)hipStreamDestroy(stream); }
     for (void *m : mem) if (m) (void)hipFree(m);
+    if (sink) (void)hipFree(sink);
     if (rc != HP_OK) return rc;
     *gbps_out = (double)(n_read + n_write) * (double)bytes_per_array / ((double)best_ms * 1e-3) / 1e9;
     if (best_shape) {
@@ -1407,6 +1418,6 @@ const char *hp_strerror(int code) {
 
 int hp_last_hip_error(void) { return g_last_hip_error; }
 
-const char *hp_version(void) { return "hp-boundary 0.3 (gfx950)"; }
+const char *hp_version(void) { return "hp-boundary 0.4 (gfx950)"; }
 
 }  // extern "C"

@@ -59,3 +59,36 @@ def test_header_is_plain_c(compiler, std, tmp_path):
                         str(src), "-o", str(exe)], capture_output=True, text=True, timeout=120)
     assert r.returncode == 0, r.stderr
     assert subprocess.run([str(exe)], timeout=30).returncode == 0
+
+
+def test_counter_traffic_is_quoted_only_for_the_sources_and_shapes_it_was_measured_with(tmp_path, monkeypatch):
+    """bench.py's roofline.traffic comes from a committed rocprofv3 summary; it
+    must turn into null as soon as the kernel sources or a launch shape differ
+    from what the summary records."""
+    sys.path.insert(0, ROOT)
+    import bench
+    monkeypatch.setattr(bench, "PROFILES", str(tmp_path))
+    shapes = {"fwd": dict(tile_bytes=2048, block_threads=64, waves_per_cu=12, nontemporal=2),
+              "bwd": dict(tile_bytes=1024, block_threads=64, waves_per_cu=16, nontemporal=3)}
+
+    def write(digest, fwd="2048,64,12,2", bwd="1024,64,16,3"):
+        (tmp_path / "hbm_traffic_long_context.txt").write_text(
+            "# comment = ignored\nhead = abc1234\nkernel_sources_sha256 = %s\nshape_fwd = %s\nshape_bwd = %s\n"
+            "forward_bytes_per_launch = 2055420910     # algorithmic 2055116800\nbackward_bytes_per_launch = 2055260453\n"
+            "forward_bytes_per_boundary_byte = 5.0007\nbackward_bytes_per_boundary_byte = 5.0003\n" % (digest, fwd, bwd))
+
+    assert bench.traffic_for("long_context", shapes, "hp_forward_kernel") == (None, None, None)     # no summary at all
+    write(bench.kernel_source_digest())
+    t, per, src = bench.traffic_for("long_context", shapes, "hp_forward_kernel")
+    assert (t, per) == (2055420910.0, 5.0007) and src["matches_this_run"] and src["head"] == "abc1234"
+    assert src["file"] == "profiles/hbm_traffic_long_context.txt" and src["shapes"]["fwd"] == "2048,64,12,2"
+    t, per, _ = bench.traffic_for("long_context", shapes, "hp_backward_kernel")
+    assert (t, per) == (2055260453.0, 5.0003)
+    other = {"fwd": dict(shapes["fwd"], waves_per_cu=8), "bwd": shapes["bwd"]}                      # another launch shape
+    t, per, src = bench.traffic_for("long_context", other, "hp_forward_kernel")
+    assert t is None and per is None and src["matches_this_run"] is False
+    write("0" * 64)                                                                                 # other kernel sources
+    t, per, src = bench.traffic_for("long_context", shapes, "hp_forward_kernel")
+    assert t is None and src["matches_this_run"] is False
+    assert bench.traffic_label(dict(workload="long_context", accumulate=True)) == "long_context_accumulate"
+    assert bench.traffic_label(dict(workload="large_scale", seq_shard=True, dtype="f32")) == "large_scale_seq_shard_f32"

@@ -475,6 +475,15 @@ def test_stream_probe_reports_a_rate():
     assert gbps2 > 50.0 and shape2 == fixed
     with pytest.raises(hp.HpError):
         hp.hp_probe_stream(9, 1, 8 << 20)
+    # other tile schedules of the probe (ragged sizes: the last tile and the last XCD share are partial)
+    for sched in ("oneshot", "xcd_chunked", "persistent", "persistent_xcd"):
+        for nbytes in (8 << 20, (8 << 20) + 4096 + 16, 65536):
+            assert hp.hp_probe_stream_ex(1, 4, nbytes, fixed, sched) > 1.0
+            assert hp.hp_probe_stream_ex(2, 0, nbytes, dict(fixed, block_threads=256, tile_bytes=8192), sched) > 1.0
+    with pytest.raises(hp.HpError):
+        hp.hp_probe_stream_ex(0, 0, 8 << 20, fixed, 0)
+    with pytest.raises(hp.HpError):
+        hp.hp_probe_stream_ex(1, 1, 8 << 20, fixed, 7)
 
 
 # ---- binary32 payloads and the accumulating backward ---------------------------
