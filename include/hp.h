@@ -414,12 +414,19 @@ int hp_probe_stream(int32_t n_read, int32_t n_write, int64_t bytes_per_array,
  *                            waves_per_cu is 0); each workgroup loops over the
  *                            tiles with the grid size as stride;
  *   HP_PROBE_PERSISTENT_XCD  persistent, each XCD's workgroups stride through
- *                            their own contiguous eighth.
+ *                            their own contiguous eighth;
+ *   HP_PROBE_PHASED          persistent, and a workgroup loads its whole tile
+ *                            (4, 8 or 16 sixteen-byte chunks per lane, i.e.
+ *                            tile_bytes = 64, 128 or 256 x block_threads) into
+ *                            registers before its first store: reads and
+ *                            writes reach HBM in long separate bursts
+ *                            (n_read <= 1, n_write >= 1).
  * Otherwise as hp_probe_stream (allocates its own buffers, SYNCHRONOUS). */
 #define HP_PROBE_ONESHOT        0
 #define HP_PROBE_XCD_CHUNKED    1
 #define HP_PROBE_PERSISTENT     2
 #define HP_PROBE_PERSISTENT_XCD 3
+#define HP_PROBE_PHASED         4
 int hp_probe_stream_ex(int32_t n_read, int32_t n_write, int64_t bytes_per_array,
                        const hp_launch_t *shape, int32_t schedule, double *gbps_out);
 

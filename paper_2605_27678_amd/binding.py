@@ -175,7 +175,7 @@ def hp_probe_stream(n_read: int, n_write: int, bytes_per_array: int, shape: Opti
     return out.value, {f[0]: getattr(best, f[0]) for f in best._fields_}
 
 
-PROBE_SCHEDULES = {"oneshot": 0, "xcd_chunked": 1, "persistent": 2, "persistent_xcd": 3}
+PROBE_SCHEDULES = {"oneshot": 0, "xcd_chunked": 1, "persistent": 2, "persistent_xcd": 3, "phased": 4}
 
 
 def hp_probe_stream_ex(n_read: int, n_write: int, bytes_per_array: int, shape: dict, schedule) -> float:

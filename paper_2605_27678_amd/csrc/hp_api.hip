@@ -321,12 +321,15 @@ __device__ __forceinline__ void probe_group(const ProbeArgs &a, uint64_t base, u
     }
     for (uint32_t r0 = 0; r0 < a.n_read; r0 += 4) {
         u32x4 v[4][U];
+        // the array count is uniform over the launch: these branches are scalar, and the loads of a
+        // group are still issued back to back before the first use
 #pragma unroll
-        for (int g = 0; g < 4; ++g) {
-            const u32x4 *p = a.rd[min(r0 + g, a.n_read - 1)] + base;
+        for (int g = 0; g < 4; ++g)
+            if (r0 + g < a.n_read) {
+                const u32x4 *p = a.rd[r0 + g] + base;
 #pragma unroll
-            for (int u = 0; u < U; ++u) v[g][u] = ld<u32x4, NTL>(p + (GUARD ? min(i[u], n - 1) : i[u]));
-        }
+                for (int u = 0; u < U; ++u) v[g][u] = ld<u32x4, NTL>(p + (GUARD ? min(i[u], n - 1) : i[u]));
+            }
 #pragma unroll
         for (int g = 0; g < 4; ++g)
             if (r0 + g < a.n_read) {
@@ -348,6 +351,22 @@ __device__ __forceinline__ void probe_group(const ProbeArgs &a, uint64_t base, u
     }
 }
 
+// A whole tile of U chunks per lane from at most one read array into registers, then to every write
+// array (the phased schedule).
+template <int U, bool NTL, bool NTS>
+__device__ __forceinline__ void probe_deep(const ProbeArgs &a, uint64_t base) {
+    u32x4 v[U];
+#pragma unroll
+    for (int u = 0; u < U; ++u) {
+        v[u] = (u32x4){1u, 2u, 3u, 4u};
+        if (a.n_read) v[u] = ld<u32x4, NTL>(a.rd[0] + base + u * blockDim.x + threadIdx.x);
+    }
+    for (uint32_t w = 0; w < a.n_write; ++w) {
+#pragma unroll
+        for (int u = 0; u < U; ++u) st<u32x4, NTS>(a.wr[w] + base + u * blockDim.x + threadIdx.x, v[u]);
+    }
+}
+
 template <bool NTL, bool NTS>
 __device__ __forceinline__ void probe_tile(const ProbeArgs &a, uint32_t tile) {
     const uint64_t base = (uint64_t)tile * a.chunks_per_wg;
@@ -365,6 +384,7 @@ __device__ __forceinline__ void probe_tile(const ProbeArgs &a, uint32_t tile) {
 //   XCD-chunked    one-shot, but the workgroups that land on one XCD walk one contiguous eighth of the tiles
 //   persistent     a grid of a few workgroups per CU; each loops over the tiles with the grid as stride
 //   persistent+XCD persistent, each XCD's workgroups stride through their own contiguous eighth
+//   phased         persistent, whole tiles loaded into registers before their first store
 // Every loop is bounded by n_tiles and every workgroup leaves it.
 template <bool NTL, bool NTS, int SCHED>
 __global__ void __launch_bounds__(1024) hp_probe_kernel(const ProbeArgs a) {
@@ -375,6 +395,19 @@ __global__ void __launch_bounds__(1024) hp_probe_kernel(const ProbeArgs a) {
         if (blockIdx.x / kXcds < a.tiles_per_xcd && tile < a.n_tiles) probe_tile<NTL, NTS>(a, tile);
     } else if constexpr (SCHED == HP_PROBE_PERSISTENT) {
         for (uint32_t tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) probe_tile<NTL, NTS>(a, tile);
+    } else if constexpr (SCHED == HP_PROBE_PHASED) {
+        // persistent, and a whole tile (up to 16 chunks per lane) is loaded into registers before the
+        // first store: long read bursts followed by long write bursts, in step over the chip as far
+        // as equal work keeps the workgroups in step
+        const uint32_t per_lane = a.chunks_per_wg / blockDim.x;
+        for (uint32_t tile = blockIdx.x; tile < a.n_tiles; tile += gridDim.x) {
+            const uint64_t base = (uint64_t)tile * a.chunks_per_wg;
+            const bool whole = a.n_chunks - base >= a.chunks_per_wg && per_lane * blockDim.x == a.chunks_per_wg;
+            if (whole && per_lane == 16) probe_deep<16, NTL, NTS>(a, base);
+            else if (whole && per_lane == 8) probe_deep<8, NTL, NTS>(a, base);
+            else if (whole && per_lane == 4) probe_deep<4, NTL, NTS>(a, base);
+            else probe_tile<NTL, NTS>(a, tile);
+        }
     } else {
         const uint32_t xcd = blockIdx.x % kXcds, stride = gridDim.x / kXcds;     // grid is a multiple of kXcds
         for (uint32_t t = blockIdx.x / kXcds; t < a.tiles_per_xcd; t += stride) {
@@ -961,6 +994,7 @@ void launch_probe(const ProbeArgs &args, const LaunchCfg &c, int nontemporal, in
         case HP_PROBE_ONESHOT: launch_probe_sched<HP_PROBE_ONESHOT>(args, c, nontemporal); break;
         case HP_PROBE_XCD_CHUNKED: launch_probe_sched<HP_PROBE_XCD_CHUNKED>(args, c, nontemporal); break;
         case HP_PROBE_PERSISTENT: launch_probe_sched<HP_PROBE_PERSISTENT>(args, c, nontemporal); break;
+        case HP_PROBE_PHASED: launch_probe_sched<HP_PROBE_PHASED>(args, c, nontemporal); break;
         default: launch_probe_sched<HP_PROBE_PERSISTENT_XCD>(args, c, nontemporal); break;
     }
 }
@@ -1222,7 +1256,8 @@ namespace {
 int probe_stream(int32_t n_read, int32_t n_write, int64_t bytes_per_array, const hp_launch_t *shape,
                  int schedule, double *gbps_out, hp_launch_t *best_shape) {
     if (n_read < 0 || n_read > 8 || n_write < 0 || n_write > 8 || n_read + n_write < 1 || !gbps_out) return HP_EINVAL;
-    if (schedule < HP_PROBE_ONESHOT || schedule > HP_PROBE_PERSISTENT_XCD) return HP_EINVAL;
+    if (schedule < HP_PROBE_ONESHOT || schedule > HP_PROBE_PHASED) return HP_EINVAL;
+    if (schedule == HP_PROBE_PHASED && (n_read > 1 || n_write < 1)) return HP_EINVAL;   // one read stream at most
     if (bytes_per_array > 0 && bytes_per_array / 1024 > 0x7fffffff) return HP_EINVAL;   // tile count in 32 bits
     if (bytes_per_array < 65536 || bytes_per_array % 16 || bytes_per_array > ((int64_t)1 << 36)) return HP_EINVAL;
     hp::Launch fixed{};

@@ -476,14 +476,20 @@ def test_stream_probe_reports_a_rate():
     with pytest.raises(hp.HpError):
         hp.hp_probe_stream(9, 1, 8 << 20)
     # other tile schedules of the probe (ragged sizes: the last tile and the last XCD share are partial)
-    for sched in ("oneshot", "xcd_chunked", "persistent", "persistent_xcd"):
+    for sched in ("oneshot", "xcd_chunked", "persistent", "persistent_xcd", "phased"):
         for nbytes in (8 << 20, (8 << 20) + 4096 + 16, 65536):
             assert hp.hp_probe_stream_ex(1, 4, nbytes, fixed, sched) > 1.0
-            assert hp.hp_probe_stream_ex(2, 0, nbytes, dict(fixed, block_threads=256, tile_bytes=8192), sched) > 1.0
+            if sched != "phased":                                # phased: one read stream at most, one write at least
+                assert hp.hp_probe_stream_ex(2, 0, nbytes, dict(fixed, block_threads=256, tile_bytes=8192), sched) > 1.0
     with pytest.raises(hp.HpError):
         hp.hp_probe_stream_ex(0, 0, 8 << 20, fixed, 0)
     with pytest.raises(hp.HpError):
         hp.hp_probe_stream_ex(1, 1, 8 << 20, fixed, 7)
+    with pytest.raises(hp.HpError):
+        hp.hp_probe_stream_ex(2, 1, 8 << 20, fixed, "phased")
+    for tile, block in ((65536, 256), (65536, 512), (65536, 1024), (16384, 256)):      # 16, 8, 4, 4 chunks per lane
+        deep = dict(tile_bytes=tile, block_threads=block, waves_per_cu=16, nontemporal=2)
+        assert hp.hp_probe_stream_ex(1, 4, (8 << 20) + 4096 + 16, deep, "phased") > 1.0
 
 
 # ---- binary32 payloads and the accumulating backward ---------------------------
