@@ -263,6 +263,69 @@ def test_profile_records_kernel_durations():
         assert torch.equal(a.float(), 4.0 * b.float())    # four identical replicas summed: exact in bf16
 
 
+def _guarded(rows, hidden, dtype, fill, guard=3):
+    """A [rows, hidden] buffer cut out of a larger allocation whose `guard` rows
+    before and after it hold a sentinel: (buffer view, whole allocation)."""
+    whole = torch.full((rows + 2 * guard, hidden), fill, dtype=dtype, device="cuda")
+    return whole[guard:guard + rows], whole
+
+
+@pytest.mark.parametrize("case", ["random0", "random1", "random2", "random3", "long_context_h328", "sbh_short_rows",
+                                  "seq_shard", "accumulate_f32"])
+def test_guard_rows_around_every_buffer_stay_untouched(case):
+    """Every buffer of a call sits between sentinel rows; forward, backward and
+    the accumulating backward must leave all of them as found (an access past a
+    buffer's end that lands in unrelated memory would go unnoticed by the
+    whole-buffer comparisons)."""
+    rng = np.random.default_rng(abs(hash(case)) % 1000)
+    acc = case == "accumulate_f32"
+    if case.startswith("random"):
+        src, dst, tm = wl.random_layout_case(np.random.default_rng(900 + int(case[-1])))
+    elif case == "sbh_short_rows":
+        src, dst = wl.Grid(tp=2, dp=2), wl.Grid(tp=2, cp=2, dp=1, cp_split=wl.CP_ZIGZAG, row_order=wl.ROW_SBH)
+        tm = wl.token_map_from_lens(rng, 4, 64, 24, [[5, 9], [17], [], [3, 3, 3]])
+    else:
+        w = wl.scaled(wl.long_context(), 328)                    # 656-byte rows: 16-byte lanes, ragged tiles
+        src, dst, tm = w.src, w.dst, w.maps[0]
+        if case == "seq_shard":
+            dst = replace(dst, tp_mode=wl.TP_SEQ_SHARD)
+    plan = hp.hp_plan_create(src, dst, tm)
+    H, drows = tm.hidden, plan.info.dst_rows_per_buf
+    S = 0x7FC5
+    mk = lambda rows, dt, fill: _guarded(rows, H, dt, fill)
+    bf = torch.bfloat16
+    srcs = [mk(r, bf, 1.5) for r in plan.src_rows()]
+    dsts = [mk(drows, bf, 2.5) for _ in range(plan.info.n_dst_bufs)]
+    grads = [mk(drows, bf, 0.25) for _ in range(plan.info.n_dst_bufs)]
+    sgs = [mk(r, torch.float32 if acc else bf, 7.0) for r in plan.src_rows()]
+    for view, whole in srcs + dsts + grads + sgs:                # sentinels into the guard rows only
+        raw = whole.view(torch.int16) if whole.dtype == bf else whole
+        raw[:3] = S if whole.dtype == bf else -123.0
+        raw[-3:] = S if whole.dtype == bf else -123.0
+    torch.cuda.synchronize()
+    hp.hp_forward(plan, [v for v, _ in srcs], [v for v, _ in dsts])
+    if acc:
+        hp.hp_backward_accumulate(plan, [v for v, _ in grads], [v for v, _ in sgs])
+    else:
+        hp.hp_backward(plan, [v for v, _ in grads], [v for v, _ in sgs])
+    hp.hp_forward_static(plan, [v for v, _ in srcs], [v for v, _ in dsts])
+    torch.cuda.synchronize()
+    for name, group in (("source", srcs), ("destination", dsts), ("gradient", grads), ("source gradient", sgs)):
+        for i, (view, whole) in enumerate(group):
+            g = torch.cat([whole[:3], whole[-3:]])
+            if whole.dtype == bf:
+                assert bool((g.view(torch.int16) == torch.tensor(S, dtype=torch.int16)).all()), (name, i)
+            else:
+                assert bool((g == -123.0).all()), (name, i)
+    # and the calls did their work: image rows moved (1.5), source gradients written
+    n_img = sum(int((v == 1.5).all(dim=1).sum()) for v, _ in dsts)
+    assert n_img == plan.info.dst_copies * tm.n_rows
+    want = (0.25 * plan.info.dst_copies) + (7.0 if acc else 0.0)
+    for (v, _), r in zip(sgs, plan.src_rows()):
+        assert r == 0 or bool((v == want).all())
+    plan.close()
+
+
 # ---- full sizes, in the launch configuration the benchmark times --------------
 
 def test_full_colocated4():
