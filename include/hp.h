@@ -377,8 +377,8 @@ int hp_plan_tune_accumulate(hp_plan_t *plan, const void *const *dst_grad_bufs,
  * Keys: "tile_bytes_fwd", "tile_bytes_bwd", "block_threads_fwd",
  * "block_threads_bwd", "waves_per_cu_fwd", "waves_per_cu_bwd",
  * "nontemporal_fwd", "nontemporal_bwd"; meanings and ranges as in hp_launch_t.
- * The tile size and the resident-wave cap also take HP_AUTO (-1, their initial
- * value): the plan then picks them from its replica counts - the more buffers a
+ * The tile size, the workgroup size and the resident-wave cap also take HP_AUTO
+ * (-1, their initial value): the plan then picks them from its replica counts - the more buffers a
  * row's traffic spreads over (1 + TP_dst forward, TP_dst + TP_src backward) the
  * lower the cap, so that about 100 KB per compute unit stay in flight; the
  * figures are what hp_plan_tune finds most often per replica count.

@@ -545,8 +545,7 @@ void launch_backward_shape(int dtype, bool acc, int elems, int copies, const Lau
             else launch_backward_nrep<HP_F32, 1, false, NTL, NTS>(copies, c, bt, k);
         }
     } else if (acc) {
-        if (elems == 8) launch_backward_nrep<HP_BF16, 8, true, NTL, NTS>(copies, c, bt, k);
-        else if (elems == 4) launch_backward_nrep<HP_BF16, 4, true, NTL, NTS>(copies, c, bt, k);
+        if (elems == 4) launch_backward_nrep<HP_BF16, 4, true, NTL, NTS>(copies, c, bt, k);
         else launch_backward_nrep<HP_BF16, 1, true, NTL, NTS>(copies, c, bt, k);
     } else {
         if (elems == 8) launch_backward_nrep<HP_BF16, 8, false, NTL, NTS>(copies, c, bt, k);
@@ -632,9 +631,12 @@ int prepare(const hp_plan *p, Direction dir, const void *const *src, const void 
     }
     const uint64_t eb = (uint64_t)p->elem_bytes;
     if (dir == kBackwardAcc) {
-        // bf16 gradients: 16-byte loads, two 16-byte accumulator chunks per lane
-        if (eb == 2 && ((dst_bits & 15) | (src_bits & 31)) == 0) *lane = 8;
-        else if (((dst_bits & (4 * eb - 1)) | (src_bits & 15)) == 0) *lane = 4;
+        // Four elements per lane: one 16-byte chunk of binary32 accumulators per lane, so that every
+        // accumulator load and store instruction of a wave covers 1 KiB without gaps (bf16 gradients
+        // then come in 8-byte pieces).  Eight bf16 elements per lane would pair a 16-byte gradient load
+        // with 32 bytes of accumulators per lane, i.e. two half-covered store instructions per line:
+        // measured 6 % more HBM write traffic and 3-6 % less throughput.
+        if (((dst_bits & (4 * eb - 1)) | (src_bits & 15)) == 0) *lane = 4;
         else if (((dst_bits & (eb - 1)) | (src_bits & 3)) == 0) *lane = 1;
         else return HP_EALIGN;
     } else {
@@ -844,8 +846,8 @@ struct OptionDesc {
 const OptionDesc kOptions[] = {
     {"tile_bytes_fwd", &hp::Options::tile_bytes_fwd, -1, 65536, 1, true},
     {"tile_bytes_bwd", &hp::Options::tile_bytes_bwd, -1, 65536, 1, true},
-    {"block_threads_fwd", &hp::Options::block_threads_fwd, 64, 1024, 64, false},
-    {"block_threads_bwd", &hp::Options::block_threads_bwd, 64, 1024, 64, false},
+    {"block_threads_fwd", &hp::Options::block_threads_fwd, -1, 1024, 64, false},
+    {"block_threads_bwd", &hp::Options::block_threads_bwd, -1, 1024, 64, false},
     {"nontemporal_fwd", &hp::Options::nontemporal_fwd, 0, 3, 1, false},
     {"nontemporal_bwd", &hp::Options::nontemporal_bwd, 0, 3, 1, false},
     {"waves_per_cu_fwd", &hp::Options::waves_per_cu_fwd, -1, 32, 1, false},
@@ -1373,7 +1375,8 @@ int hp_set_option(const char *key, int64_t value) {
     if (!key) return HP_EINVAL;
     for (const OptionDesc &d : kOptions) {
         if (std::strcmp(key, d.name)) continue;
-        if (value < d.lo || value > d.hi || (d.multiple > 1 && value % d.multiple)) return HP_EINVAL;
+        if (value < d.lo || value > d.hi) return HP_EINVAL;
+        if (d.multiple > 1 && value != HP_AUTO && (value < d.multiple || value % d.multiple)) return HP_EINVAL;
         if (d.tile && value != HP_AUTO && hp::tile_variant_of(value) < 0) return HP_EINVAL;
         std::lock_guard<std::mutex> lk(hp::options_mutex());
         hp::options().*(d.field) = value;

@@ -215,14 +215,16 @@ void default_launches(hp_plan *p) {
         o = options();
     }
     const int c = p->dst_copies, s = p->src_copies;
-    Launch f{1, 64, c <= 1 ? 24 : c == 2 ? 14 : c <= 4 ? 12 : c <= 7 ? 8 : 5, 2};          // 2 KiB tiles
+    Launch f{1, 64, c <= 1 ? 24 : c <= 4 ? 12 : c <= 7 ? 8 : 5, 2};                          // 2 KiB tiles
+    if (c == 2) f = Launch{2, 256, 28, 2};      // two copies: 4 KiB tiles, 256 lanes (+3.6 % on config 4 over 2 KiB x 64, cap 14)
     Launch b = c + s <= 2 ? Launch{1, 64, 30, 3} : c + s == 3 ? Launch{0, 64, 30, 3} : Launch{0, 64, 16, 3};
-    // accumulating backward: the binary32 accumulators are read and written, 2 * 4 / elem_bytes row sizes per copy
+    // accumulating backward: the binary32 accumulators are read and written, 2 * 4 / elem_bytes row sizes per copy;
+    // caps as the measured search finds them for 6, 8 and 16 streams (configs 4, 3 and 5)
     const int acc_streams = c + s * 8 / p->elem_bytes;
-    Launch a{1, 64, std::min(24, std::max(4, (100 + acc_streams / 2) / acc_streams)), 3};
+    Launch a{1, 64, acc_streams <= 4 ? 16 : acc_streams <= 6 ? 13 : acc_streams <= 8 ? 11 : acc_streams <= 12 ? 9 : 7, 3};
     auto apply = [](Launch &L, int64_t tile, int64_t block, int64_t waves, int64_t nt) {
         if (tile > 0) L.tile_variant = tile_variant_of(tile);
-        L.block = (int32_t)block;
+        if (block > 0) L.block = (int32_t)block;
         if (waves >= 0) L.waves_per_cu = (int32_t)waves;
         L.nontemporal = (int32_t)nt;
     };

@@ -57,7 +57,7 @@ struct Launch {
 struct Options {
     // HP_AUTO (-1) = chosen per plan from its replica counts (see default_launch)
     int64_t tile_bytes_fwd = -1, tile_bytes_bwd = -1;
-    int64_t block_threads_fwd = 64, block_threads_bwd = 64;
+    int64_t block_threads_fwd = -1, block_threads_bwd = -1;
     int64_t waves_per_cu_fwd = -1, waves_per_cu_bwd = -1;   // 0 = no cap
     int64_t nontemporal_fwd = 2, nontemporal_bwd = 3;       // bit 0 loads, bit 1 stores
 };

@@ -186,7 +186,9 @@ def test_null_arguments_and_host_only_state():
     assert L.hp_set_option(b"tile_bytes_fwd", 3000) == binding.HP_EINVAL
     assert L.hp_set_option(b"tile_bytes_bwd", 131072) == binding.HP_EINVAL
     assert L.hp_set_option(b"waves_per_cu_bwd", 33) == binding.HP_EINVAL
-    assert hp.hp_get_option("block_threads_fwd") % 64 == 0
+    assert hp.hp_get_option("block_threads_fwd") in (-1, 64, 128, 256, 512, 1024)
+    assert L.hp_set_option(b"block_threads_fwd", 0) == binding.HP_EINVAL
+    assert L.hp_set_option(b"block_threads_fwd", -2) == binding.HP_EINVAL
     assert hp.hp_get_option("nope") == -2 ** 63
     assert L.hp_profile_enable(-1) == binding.HP_EINVAL
     assert L.hp_profile_enable(0) == binding.HP_OK
@@ -343,10 +345,10 @@ def test_default_launch_shapes_follow_the_replica_counts():
     for tp in (1, 2, 4, 8, 16):
         p = hp.hp_plan_create_host(wl.Grid(), wl.Grid(tp=tp), tm)
         f, b, a = p.get_launch(0), p.get_launch(1), p.get_launch(2)
-        assert f["tile_bytes"] == 2048 and f["block_threads"] == 64 and f["nontemporal"] == 2
+        assert (f["tile_bytes"], f["block_threads"]) == ((4096, 256) if tp == 2 else (2048, 64)) and f["nontemporal"] == 2
         assert b["tile_bytes"] in (1024, 2048) and b["nontemporal"] == 3
         assert 4 <= a["waves_per_cu"] <= 24 and a["tile_bytes"] == 2048
-        caps_f.append(f["waves_per_cu"])
+        caps_f.append(f["waves_per_cu"] * 2048 // f["tile_bytes"])          # workgroups of 2 KiB-equivalents per CU
         caps_b.append(b["waves_per_cu"] * b["tile_bytes"])
     assert caps_f == sorted(caps_f, reverse=True) and caps_f[0] > caps_f[-1]
     assert caps_b == sorted(caps_b, reverse=True)
@@ -354,6 +356,10 @@ def test_default_launch_shapes_follow_the_replica_counts():
                                 wl.TokenMap(1, 64, 64, [0], [8], [16]))
     assert lc.get_launch(0) == dict(tile_bytes=2048, block_threads=64, waves_per_cu=12, nontemporal=2)
     assert lc.get_launch(1) == dict(tile_bytes=1024, block_threads=64, waves_per_cu=16, nontemporal=3)
+    assert lc.get_launch(2) == dict(tile_bytes=2048, block_threads=64, waves_per_cu=11, nontemporal=3)
+    caps_a = [hp.hp_plan_create_host(wl.Grid(tp=ts), wl.Grid(tp=td), tm).get_launch(2)["waves_per_cu"]
+              for ts, td in ((1, 1), (1, 2), (1, 4), (2, 4), (2, 8), (2, 16))]       # 5, 6, 8, 12, 16, 24 streams
+    assert caps_a == [13, 13, 11, 9, 7, 7]
     saved = {k: hp.hp_get_option(k) for k in ("tile_bytes_fwd", "waves_per_cu_bwd", "tile_bytes_bwd")}
     assert set(saved.values()) == {-1}
     try:
