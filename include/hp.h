@@ -394,8 +394,9 @@ int64_t hp_get_option(const char *key);     /* INT64_MIN for an unknown key */
  * workgroups and occupancy cap as the transform kernels but no segment lookup:
  * the practical ceiling of hp_forward's 1-read : TP_dst-write pattern and of
  * hp_backward's TP_dst-read : TP_src-write pattern on this machine.  With
- * shape == NULL it searches the launch shapes hp_plan_tune searches and
- * reports the best (also in *best_shape if not NULL); otherwise it times the
+ * shape == NULL it searches the launch shapes hp_plan_tune searches (one burst
+ * each, then the best five again by the median of three bursts) and reports
+ * the best (also in *best_shape if not NULL); otherwise it times the
  * given shape.  *gbps_out receives (n_read + n_write) * bytes / best time in
  * GB/s.  Allocates and frees its own device buffers, stream and events;
  * SYNCHRONOUS. */
