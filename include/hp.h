@@ -281,6 +281,19 @@ int hp_forward(const hp_plan_t *plan, const void *const *src_bufs,
 int hp_backward(const hp_plan_t *plan, const void *const *dst_grad_bufs,
                 void *const *src_grad_bufs, void *stream);
 
+/* hp_zero_image_rows - sets exactly the image-token rows of every destination-
+ * shaped buffer to zero (all dst_copies copies; every other byte is left as
+ * found).  The rows that hp_forward inserts do not depend on the text
+ * embeddings that were there before (appendix "Pipeline schedule details",
+ * phase 2: the boundary view is put into the microbatch's text embeddings at the
+ * image positions), so the gradient of the fused sequence with respect to those
+ * text embeddings is the destination gradient with these rows blanked: an
+ * autograd wrapper around hp_forward / hp_backward calls this on a copy of the
+ * destination gradients after hp_backward has read them.
+ *   dst_bufs: HOST array of n_dst_bufs DEVICE pointers, shapes as for hp_forward.
+ * Uses hp_forward's launch shape; allocates nothing; returns after enqueueing. */
+int hp_zero_image_rows(const hp_plan_t *plan, void *const *dst_bufs, void *stream);
+
 /* hp_backward_accumulate - as hp_backward, but the source side holds binary32
  * gradient ACCUMULATORS that are added to instead of overwritten: the gradients
  * that accumulate on the packed boundary tensor over the microbatches of a

@@ -259,6 +259,28 @@ int orc_forward(const orc_grid_t *src, const orc_grid_t *dst, const orc_map_t *m
     return 0;
 }
 
+/* The rows that forward writes, set to zero in every destination buffer (all TP
+ * copies), everything else left as found: the gradient of the fused sequence
+ * with respect to the text embeddings it was built on has no contribution at the
+ * image positions, because forward replaces those rows ("Pipeline schedule
+ * details", phase 2: the boundary view is inserted into the text embeddings). */
+int orc_zero_image_rows(const orc_grid_t *src, const orc_grid_t *dst, const orc_map_t *m,
+                        int32_t elem_size, void *const *dst_bufs)
+{
+    if (check_shapes(src, dst, m)) return -1;
+    const size_t row_bytes = (size_t)elem_size * (size_t)m->hidden;
+    const int32_t n_dst = dst->tp * dst->cp * dst->dp;
+    const int64_t rows = orc_dst_rows(dst, m);
+    for (int32_t buf = 0; buf < n_dst; ++buf)
+        for (int64_t r = 0; r < rows; ++r) {
+            int32_t b, k, j; int64_t s;
+            dst_global(dst, m, buf, r, &b, &s);
+            if (find_image(m, b, s, &k, &j))
+                memset((char *)dst_bufs[buf] + (size_t)r * row_bytes, 0, row_bytes);
+        }
+    return 0;
+}
+
 /* Backward for either gradient dtype (0 = bf16, 1 = binary32), overwriting or
  * accumulating.  Same walk and same ascending-tp binary32 left fold as
  * orc_backward_bf16 below.  Overwrite: the sum is rounded to the gradient dtype

@@ -133,6 +133,17 @@ class Problem:
         if rc:
             raise ValueError("oracle: layout does not divide the token map")
 
+    def zero_image_rows(self, dst_bufs: Sequence[np.ndarray]) -> None:
+        """In place: the image-token rows of every destination buffer become zero."""
+        assert len(dst_bufs) == self.n_dst
+        es = dst_bufs[0].dtype.itemsize
+        for a in dst_bufs:
+            assert a.dtype.itemsize == es and a.size == self.dst_rows() * self.hidden
+        rc = lib().orc_zero_image_rows(C.byref(self.src), C.byref(self.dst), C.byref(self.map),
+                                       C.c_int32(es), self._ptrs(dst_bufs))
+        if rc:
+            raise ValueError("oracle: layout does not divide the token map")
+
     def backward_bf16(self, dst_grads: Sequence[np.ndarray], src_grads: Sequence[np.ndarray]) -> None:
         """uint16 bf16 bit patterns in, uint16 out (in place on src_grads)."""
         assert len(dst_grads) == self.n_dst and len(src_grads) == self.n_src

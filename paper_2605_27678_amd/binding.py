@@ -69,7 +69,7 @@ EXPORTS = ["hp_plan_create", "hp_plan_create_host", "hp_plan_create_batched", "h
            "hp_plan_destroy",
            "hp_release_cached_memory", "hp_forget_tuned_shapes",
            "hp_plan_query", "hp_plan_src_rows", "hp_plan_segments", "hp_plan_get_launch",
-           "hp_plan_set_launch", "hp_plan_tune", "hp_plan_tune_accumulate", "hp_forward", "hp_backward", "hp_backward_accumulate", "hp_forward_static",
+           "hp_plan_set_launch", "hp_plan_tune", "hp_plan_tune_accumulate", "hp_forward", "hp_backward", "hp_backward_accumulate", "hp_forward_static", "hp_zero_image_rows",
            "hp_set_option", "hp_get_option", "hp_probe_stream", "hp_probe_stream_ex", "hp_profile_enable", "hp_profile_read",
            "hp_strerror", "hp_last_hip_error", "hp_version"]
 
@@ -109,6 +109,8 @@ def _lib():
     L.hp_plan_segments.argtypes = [vp, C.POINTER(hp_segment_t), i32]
     L.hp_forward.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp]
     L.hp_backward.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp]
+    L.hp_zero_image_rows.argtypes = [vp, C.POINTER(vp), vp]
+    L.hp_zero_image_rows.restype = C.c_int
     L.hp_forward_static.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp]
     L.hp_forward_static.restype = C.c_int
     L.hp_backward_accumulate.argtypes = [vp, C.POINTER(vp), C.POINTER(vp), vp]
@@ -331,6 +333,13 @@ class Plan:
         ps, pd = self._src_dst(src_bufs, dst_bufs)
         _check(_lib().hp_forward_static(self._h, ps, pd, _stream_handle(stream)), "hp_forward_static")
 
+    def zero_image_rows(self, dst_bufs: Sequence, stream=None) -> None:
+        """Zeroes the image-token rows of destination-shaped buffers in place."""
+        if len(dst_bufs) != self.info.n_dst_bufs:
+            raise ValueError("wrong number of buffers for this plan")
+        pd = self._pointers(dst_bufs, [self.info.dst_rows_per_buf] * len(dst_bufs), "dst")
+        _check(_lib().hp_zero_image_rows(self._h, pd, _stream_handle(stream)), "hp_zero_image_rows")
+
     def backward(self, dst_grad_bufs: Sequence, src_grad_bufs: Sequence, stream=None) -> None:
         ps, pd = self._src_dst(src_grad_bufs, dst_grad_bufs)
         _check(_lib().hp_backward(self._h, pd, ps, _stream_handle(stream)), "hp_backward")
@@ -398,6 +407,10 @@ def hp_forward(plan: Plan, src_bufs, dst_bufs, stream=None) -> None:
 
 def hp_forward_static(plan: Plan, src_bufs, dst_bufs, stream=None) -> None:
     plan.forward_static(src_bufs, dst_bufs, stream)
+
+
+def hp_zero_image_rows(plan: Plan, dst_bufs, stream=None) -> None:
+    plan.zero_image_rows(dst_bufs, stream)
 
 
 def hp_backward(plan: Plan, dst_grad_bufs, src_grad_bufs, stream=None) -> None:

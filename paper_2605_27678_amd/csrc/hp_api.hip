@@ -125,6 +125,31 @@ hp_forward_kernel(const KParams k, const BufTable bufs) {
 }
 
 // ---------------------------------------------------------------------------
+// zero rows: the forward's store pattern with nothing read - every image-token
+// row of every destination copy is set to zero
+// ---------------------------------------------------------------------------
+template <typename V, bool NTS>
+__global__ void __launch_bounds__(1024)
+hp_zero_rows_kernel(const KParams k, const BufTable bufs) {
+    const TileView t = locate_tile(k, blockIdx.x);
+    const uint32_t n = t.nbytes / (uint32_t)sizeof(V);
+    const V zero = {};
+    for (uint32_t r = 0; r < k.dst_copies; ++r) {
+        char *dst = (char *)bufs.p[k.dst_base + t.dst_buf0 + r] + t.dst_off;
+        if (t.pitch_rows == 1) {
+            for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) st<V, NTS>((V *)dst + i, zero);
+        } else {
+            const uint64_t pitch = (uint64_t)t.pitch_rows * k.row_bytes;
+            for (uint32_t i = threadIdx.x; i < n; i += blockDim.x) {
+                const uint32_t byte = i * (uint32_t)sizeof(V);
+                const uint32_t row = byte / k.row_bytes;
+                st<V, NTS>((V *)(dst + row * pitch + (byte - row * k.row_bytes)), zero);
+            }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
 // backward: NREP destination-gradient copies -> fp32 fold -> source copies
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ float bf16_lo(uint32_t w) { return __uint_as_float(w << 16); }
@@ -554,7 +579,7 @@ void launch_backward_shape(int dtype, bool acc, int elems, int copies, const Lau
     }
 }
 
-enum Direction { kForward = 0, kBackward = 1, kBackwardAcc = 2 };
+enum Direction { kForward = 0, kBackward = 1, kBackwardAcc = 2, kZeroRows = 3 };   // kZeroRows: forward's launch shape
 
 // Enqueues one kernel for direction `dir` with launch shape `L`.  `lane` is the
 // lane chunk chosen by prepare(): bytes for forward, elements for backward.
@@ -578,7 +603,12 @@ int enqueue_params(const hp_plan *p, Direction dir, const hp::Launch &L, const B
     c.stream = stream;
     c.ev = ev;
     const int nt = L.nontemporal & 3, copies = p->dst_copies;
-    if (dir == kForward) {
+    if (dir == kZeroRows) {
+        const bool nts = (nt & 2) != 0;
+        if (lane == 16) { if (nts) HP_LAUNCH((hp_zero_rows_kernel<u32x4, true>), c, k, bt); else HP_LAUNCH((hp_zero_rows_kernel<u32x4, false>), c, k, bt); }
+        else if (lane == 4) { if (nts) HP_LAUNCH((hp_zero_rows_kernel<uint32_t, true>), c, k, bt); else HP_LAUNCH((hp_zero_rows_kernel<uint32_t, false>), c, k, bt); }
+        else { if (nts) HP_LAUNCH((hp_zero_rows_kernel<uint16_t, true>), c, k, bt); else HP_LAUNCH((hp_zero_rows_kernel<uint16_t, false>), c, k, bt); }
+    } else if (dir == kForward) {
         switch (nt) {
             case 0: launch_forward_width<false, false>(lane, copies, c, bt, k); break;
             case 1: launch_forward_width<true, false>(lane, copies, c, bt, k); break;
@@ -607,7 +637,7 @@ int enqueue_params(const hp_plan *p, Direction dir, const hp::Launch &L, const B
 // 16-byte or 4-byte chunks).
 int prepare(const hp_plan *p, Direction dir, const void *const *src, const void *const *dst,
             BufTable *bt, int *lane, bool plan_tables = true) {
-    if (!p || !src || !dst) return HP_EINVAL;
+    if (!p || (!src && dir != kZeroRows) || !dst) return HP_EINVAL;
     if (p->segments.empty()) return HP_OK;
     if (plan_tables) {                                      // the launch will read the plan's own device tables
         if (!p->d_segs) return HP_ESTATE;
@@ -619,7 +649,7 @@ int prepare(const hp_plan *p, Direction dir, const void *const *src, const void 
     int n = 0;
     uint64_t src_bits = 0, dst_bits = (uint64_t)p->row_bytes;
     for (int i = 0; i < p->n_src_bufs; ++i) {
-        const bool needed = p->src_rows[i] > 0 && (dir != kForward || p->src_leader[i]);
+        const bool needed = dir != kZeroRows && p->src_rows[i] > 0 && (dir != kForward || p->src_leader[i]);
         if (needed && !src[i]) return HP_EINVAL;
         bt->p[n++] = needed ? const_cast<void *>(src[i]) : nullptr;
         if (needed) src_bits |= (uint64_t)(uintptr_t)src[i];
@@ -646,7 +676,7 @@ int prepare(const hp_plan *p, Direction dir, const void *const *src, const void 
         else if ((bits & 3) == 0) width = 4;
         else if ((bits & (eb - 1)) == 0) width = (int)eb;
         else return HP_EALIGN;
-        *lane = dir == kForward ? width : width / (int)eb;
+        *lane = (dir == kForward || dir == kZeroRows) ? width : width / (int)eb;
     }
     return HP_OK;
 }
@@ -1171,6 +1201,14 @@ int hp_forward(const hp_plan_t *p, const void *const *src_bufs, void *const *dst
     int rc = prepare(p, kForward, src_bufs, (const void *const *)dst_bufs, &bt, &width);
     if (rc != HP_OK || p->segments.empty()) return rc;
     return enqueue(p, kForward, p->fwd, bt, width, (hipStream_t)stream, next_event_pair(0));
+}
+
+int hp_zero_image_rows(const hp_plan_t *p, void *const *dst_bufs, void *stream) {
+    BufTable bt;
+    int width = 0;
+    int rc = prepare(p, kZeroRows, nullptr, (const void *const *)dst_bufs, &bt, &width);
+    if (rc != HP_OK || p->segments.empty()) return rc;
+    return enqueue(p, kZeroRows, p->fwd, bt, width, (hipStream_t)stream, EventPair{});
 }
 
 int hp_backward(const hp_plan_t *p, const void *const *dst_grad_bufs, void *const *src_grad_bufs,

@@ -309,8 +309,16 @@ def test_guard_rows_around_every_buffer_stay_untouched(case):
     else:
         hp.hp_backward(plan, [v for v, _ in grads], [v for v, _ in sgs])
     hp.hp_forward_static(plan, [v for v, _ in srcs], [v for v, _ in dsts])
+    zeroed = [mk(drows, bf, 4.5) for _ in range(plan.info.n_dst_bufs)]
+    for view, whole in zeroed:
+        whole.view(torch.int16)[:3] = S
+        whole.view(torch.int16)[-3:] = S
     torch.cuda.synchronize()
-    for name, group in (("source", srcs), ("destination", dsts), ("gradient", grads), ("source gradient", sgs)):
+    hp.hp_zero_image_rows(plan, [v for v, _ in zeroed])
+    torch.cuda.synchronize()
+    assert sum(int((v == 0).all(dim=1).sum()) for v, _ in zeroed) == plan.info.dst_copies * tm.n_rows
+    for name, group in (("source", srcs), ("destination", dsts), ("gradient", grads), ("source gradient", sgs),
+                        ("zeroed", zeroed)):
         for i, (view, whole) in enumerate(group):
             g = torch.cat([whole[:3], whole[-3:]])
             if whole.dtype == bf:
@@ -323,6 +331,106 @@ def test_guard_rows_around_every_buffer_stay_untouched(case):
     want = (0.25 * plan.info.dst_copies) + (7.0 if acc else 0.0)
     for (v, _), r in zip(sgs, plan.src_rows()):
         assert r == 0 or bool((v == want).all())
+    plan.close()
+
+
+@pytest.mark.parametrize("seed", range(10))
+def test_zero_image_rows_random_layouts(seed):
+    """hp_zero_image_rows against the oracle: bf16 and binary32 buffers, both TP
+    modes and row orders, whole buffers compared."""
+    rng = np.random.default_rng(1200 + seed)
+    src, dst, tm = wl.random_layout_case(rng)
+    if seed % 3 == 2 and (tm.seq // dst.cp) % dst.tp == 0:
+        dst = replace(dst, tp_mode=wl.TP_SEQ_SHARD)
+    for dtype, tdt, ndt in ((wl.DT_BF16, torch.bfloat16, np.uint16), (wl.DT_F32, torch.float32, np.float32)):
+        tmd = replace(tm, dtype=dtype)
+        plan = hp.hp_plan_create(src, dst, tmd)
+        prob = oracle.Problem(src, dst, tmd)
+        bufs = [(torch.randn((prob.dst_rows(), tm.hidden), generator=torch.Generator().manual_seed(seed * 50 + j)) + 3.0)
+                .to(tdt).cuda() for j in range(prob.n_dst)]
+        host = lambda t: (t.cpu().contiguous().view(torch.int16).numpy().view(np.uint16) if ndt is np.uint16
+                          else t.cpu().numpy()).copy()
+        want = [host(t) for t in bufs]
+        prob.zero_image_rows(want)
+        torch.cuda.synchronize()
+        hp.hp_zero_image_rows(plan, bufs)
+        torch.cuda.synchronize()
+        for j in range(prob.n_dst):
+            assert np.array_equal(host(bufs[j]), want[j]), (seed, j)
+        plan.close()
+
+
+def test_zero_image_rows_long_context_spans_and_strided_rows():
+    for hidden, order in ((328, wl.ROW_BSH), (7, wl.ROW_BSH), (2048, wl.ROW_BSH)):
+        w = wl.scaled(wl.long_context(), hidden)
+        tm = w.maps[0]
+        plan = hp.hp_plan_create(w.src, w.dst, tm)
+        prob = oracle.Problem(w.src, w.dst, tm)
+        bufs = [wl.random_bf16((prob.dst_rows(), hidden), 700 + j, "cuda") for j in range(prob.n_dst)]
+        want = [_to_host_bits(t).copy() for t in bufs]
+        prob.zero_image_rows(want)
+        torch.cuda.synchronize()
+        hp.hp_zero_image_rows(plan, bufs)
+        torch.cuda.synchronize()
+        assert all(np.array_equal(_to_host_bits(t), w_) for t, w_ in zip(bufs, want))
+        plan.close()
+    w = wl.scaled(wl.colocated4(), 24)                           # four samples per rank, [S,B,H]: row-strided segments
+    dst = replace(w.dst, row_order=wl.ROW_SBH)
+    plan = hp.hp_plan_create(w.src, dst, w.maps[0])
+    prob = oracle.Problem(w.src, dst, w.maps[0])
+    bufs = [wl.random_bf16((prob.dst_rows(), 24), 800 + j, "cuda") for j in range(prob.n_dst)]
+    want = [_to_host_bits(t).copy() for t in bufs]
+    prob.zero_image_rows(want)
+    torch.cuda.synchronize()
+    hp.hp_zero_image_rows(plan, bufs)
+    torch.cuda.synchronize()
+    assert all(np.array_equal(_to_host_bits(t), w_) for t, w_ in zip(bufs, want))
+    plan.close()
+
+
+@pytest.mark.parametrize("seed", range(6))
+def test_autograd_wrapper_against_torch_autograd_of_the_definition(seed):
+    """boundary_transform (hp_forward / hp_backward / hp_zero_image_rows under
+    torch.autograd) against CPU torch autograd of the definition written with
+    index_copy, binary32 payloads with small integers (every sum exact, so the
+    result does not depend on an accumulation order)."""
+    rng = np.random.default_rng(1300 + seed)
+    src, dst, tm = wl.random_layout_case(rng)
+    tm = replace(tm, dtype=wl.DT_F32)
+    plan = hp.hp_plan_create(src, dst, tm)
+    prob = oracle.Problem(src, dst, tm)
+    H, rows, drows = tm.hidden, prob.src_rows(), prob.dst_rows()
+    ints = lambda shape: torch.from_numpy(rng.integers(-6, 7, size=shape).astype(np.float32))
+    x_cpu = [ints((r, H)) for r in rows]
+    t_cpu = [ints((drows, H)) for _ in range(prob.n_dst)]
+    w_cpu = [ints((drows, H)) for _ in range(prob.n_dst)]           # weights of a scalar loss
+    # --- reference: the definition under CPU autograd (forward reads the leader copy tp = 0 only) ---
+    xr = [t.clone().requires_grad_(True) for t in x_cpu]
+    tr = [t.clone().requires_grad_(True) for t in t_cpu]
+    loss = 0.0
+    for j in range(prob.n_dst):
+        sb, sr = prob.forward_map(j)
+        img = np.nonzero(sb >= 0)[0]
+        out = tr[j]
+        for b in sorted(set(sb[img].tolist())):
+            sel = img[sb[img] == b]
+            out = out.index_copy(0, torch.from_numpy(sel), xr[b][torch.from_numpy(sr[sel])])
+        loss = loss + (out * w_cpu[j]).sum()
+    loss.backward()
+    # --- the library under autograd ---
+    xg = [t.clone().cuda().requires_grad_(True) for t in x_cpu]
+    tg = [t.clone().cuda().requires_grad_(True) for t in t_cpu]
+    outs = hp.boundary_transform(plan, xg, [t.clone() for t in tg])    # clones: leaves cannot be modified in place
+    gl = sum((o * w.cuda()).sum() for o, w in zip(outs, w_cpu))
+    gl.backward()
+    torch.cuda.synchronize()
+    for j in range(prob.n_dst):
+        assert torch.equal(tg[j].grad.cpu(), tr[j].grad), ("text gradient", j)
+    for i in range(prob.n_src):
+        leader = i - i % src.tp
+        want = xr[leader].grad if xr[leader].grad is not None else torch.zeros_like(x_cpu[i])
+        # every TP copy of a source rank receives the gradient of the rank's rows
+        assert torch.equal(xg[i].grad.cpu(), want), ("source gradient", i)
     plan.close()
 
 

@@ -98,6 +98,15 @@ MUTANTS = [
      "a = a + acc;", "a = a - acc;"),
     ("binary32 output rounded to bf16",
      "((float *)out)[srow * H + h] = acc;", "((float *)out)[srow * H + h] = bf16_to_f32(f32_to_bf16(acc));"),
+    # --- orc_zero_image_rows ----------------------------------------------------
+    ("zero rows: text rows blanked instead of image rows",
+     "if (find_image(m, b, s, &k, &j))\n                memset(", "if (!find_image(m, b, s, &k, &j))\n                memset("),
+    ("zero rows: only every TP-th buffer visited",
+     "for (int32_t buf = 0; buf < n_dst; ++buf)\n        for (int64_t r = 0; r < rows; ++r) {\n            int32_t b, k, j; int64_t s;",
+     "for (int32_t buf = 0; buf < n_dst; buf += dst->tp)\n        for (int64_t r = 0; r < rows; ++r) {\n            int32_t b, k, j; int64_t s;"),
+    ("zero rows: half of every row",
+     "memset((char *)dst_bufs[buf] + (size_t)r * row_bytes, 0, row_bytes);",
+     "memset((char *)dst_bufs[buf] + (size_t)r * row_bytes, 0, row_bytes / 2);"),
     ("generic backward: descending fold",
      "float g = dtype == 0 ? bf16_to_f32(((const uint16_t *)dst_grads[buf0 + t])[r * H + h])\n"
      "                                     : ((const float *)dst_grads[buf0 + t])[r * H + h];",

@@ -802,3 +802,51 @@ def test_signalling_nan_stays_nan_when_rounded_to_bf16():
     sg = [np.zeros((1, 1), np.uint16)]
     prob.backward_bf16([np.array([[0x7FA0]], np.uint16), np.array([[0x3F80]], np.uint16)], sg)
     assert (int(sg[0][0, 0]) & 0x7F80) == 0x7F80 and (int(sg[0][0, 0]) & 0x7F) != 0
+
+
+# ----------------------------------------------------------------------------
+# zeroing the inserted rows (gradient with respect to the text embeddings)
+# ----------------------------------------------------------------------------
+
+@pytest.mark.parametrize("seed", range(16))
+def test_zero_image_rows_matches_the_sliced_image_mask(seed):
+    """Expected result by slicing: the global image mask cut into the destination
+    buffers says which rows become zero; all other rows keep their content."""
+    rng = np.random.default_rng(8300 + seed)
+    if seed % 4 == 3:
+        src, dst, tm = seq_shard_case(rng)
+    else:
+        src, dst, tm = wl.random_layout_case(rng)
+    if seed % 5 == 4:
+        tm = wl.shuffle_spans(rng, tm)
+    prob = oracle.Problem(src, dst, tm)
+    for dt in (np.uint16, np.float32):
+        pre = [rng.integers(1, 60000, size=(prob.dst_rows(), tm.hidden)).astype(dt) for _ in range(prob.n_dst)]
+        got = [p.copy() for p in pre]
+        prob.zero_image_rows(got)
+        _, is_img = brute_forward(src, dst, tm, np.zeros((tm.n_rows, tm.hidden), dt), 0)
+        n_zeroed = 0
+        for j in range(prob.n_dst):
+            want = pre[j].copy()
+            want[is_img[j]] = 0
+            assert np.array_equal(got[j], want), (seed, j)
+            n_zeroed += int(is_img[j].sum())
+        assert n_zeroed == (1 if dst.tp_mode == wl.TP_SEQ_SHARD else dst.tp) * tm.n_rows
+
+
+def test_zero_image_rows_is_the_text_gradient_of_the_fused_sequence():
+    """torch autograd on the definition: fused = text with the image rows
+    replaced; d(sum(fused * g))/d(text) is g with the image rows blanked."""
+    rng = np.random.default_rng(8400)
+    tm = wl.token_map_from_lens(rng, 1, 48, 8, [[5, 9, 3]])
+    prob = oracle.Problem(wl.Grid(dp=2), wl.Grid(), tm)
+    pos = torch.from_numpy(np.concatenate([np.arange(s, s + l) for s, l in zip(tm.img_start, tm.img_len)]))
+    text = torch.randn(48, 8, requires_grad=True)
+    X = torch.randn(tm.n_rows, 8, requires_grad=True)
+    g = torch.randn(48, 8)
+    fused = text.index_copy(0, pos, X)
+    (fused * g).sum().backward()
+    got = [g.numpy().copy()]
+    prob.zero_image_rows(got)
+    assert np.array_equal(got[0], text.grad.numpy())
+    assert np.array_equal(X.grad.numpy(), g.numpy()[pos.numpy()])          # and the other half goes to the source
