@@ -582,10 +582,10 @@ def summarize_traffic(args) -> int:
             out.write(
                 f"# HBM traffic per launch of the two kernels on case {tag} (workload {workload}, variant {flags or 'plain'}),\n"
                 "# from two rocprofv3 counter passes of the same committed command (run from /tmp, TMPDIR=/tmp,\n"
-                "# repository at $R; the default run measures every case, this file keeps this case's dispatches,\n"
+                "# repository at $R, output under $OUT; the default run measures every case, this file keeps this case's dispatches,\n"
                 "# found by kernel name and grid size):\n#\n"
-                "#   rocprofv3 --pmc FETCH_SIZE -f csv -d $R/gpurun_out/prof_fetch -o bench -- python3 $R/bench.py --no-cpu-baseline --steps 3 --warmup 1\n"
-                "#   rocprofv3 --pmc WRITE_SIZE -f csv -d $R/gpurun_out/prof_write -o bench -- python3 $R/bench.py --no-cpu-baseline --steps 3 --warmup 1\n"
+                "#   rocprofv3 --pmc FETCH_SIZE -f csv -d $OUT/prof_fetch -o bench -- python3 $R/bench.py --no-cpu-baseline --steps 3 --warmup 1\n"
+                "#   rocprofv3 --pmc WRITE_SIZE -f csv -d $OUT/prof_write -o bench -- python3 $R/bench.py --no-cpu-baseline --steps 3 --warmup 1\n"
                 "#   python3 bench.py --summarize-traffic <fetch pass>/bench_counter_collection.csv <write pass>/bench_counter_collection.csv\n#\n"
                 f"# Raw counter readings (KiB per dispatch, mean; dispatches; min..max):\n"
                 f"#   hp_forward_kernel   FETCH_SIZE {ff[0]:.1f} ({ff[1]}; {ff[2]:.1f}..{ff[3]:.1f})   WRITE_SIZE {fw[0]:.1f} ({fw[1]}; {fw[2]:.1f}..{fw[3]:.1f})\n"
