@@ -92,3 +92,19 @@ def test_counter_traffic_is_quoted_only_for_the_sources_and_shapes_it_was_measur
     assert t is None and src["matches_this_run"] is False
     assert bench.traffic_label(dict(workload="long_context", accumulate=True)) == "long_context_accumulate"
     assert bench.traffic_label(dict(workload="large_scale", seq_shard=True, dtype="f32")) == "large_scale_seq_shard_f32"
+
+
+def test_plain_c_client_links_against_the_library(tmp_path):
+    """The boundary is a C ABI: a C99 program that includes only include/hp.h,
+    compiled with gcc and linked against libhp.so, builds and reads a plan."""
+    from paper_2605_27678_amd import binding
+    exe = tmp_path / "abi_client"
+    libdir = os.path.dirname(binding.LIB_PATH)
+    rocm = "/opt/rocm/lib"
+    r = subprocess.run(["gcc", "-std=c99", "-pedantic", "-Wall", "-Wextra", "-Werror", "-I", os.path.join(ROOT, "include"),
+                        os.path.join(ROOT, "tests", "abi_client.c"), "-o", str(exe),
+                        "-L", libdir, "-l:libhp.so", f"-Wl,-rpath,{libdir}", f"-Wl,-rpath-link,{rocm}", f"-Wl,-rpath,{rocm}"],
+                       capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0, r.stderr
+    r = subprocess.run([str(exe)], capture_output=True, text=True, timeout=120)
+    assert r.returncode == 0 and "abi client ok" in r.stdout, r.stdout + r.stderr
